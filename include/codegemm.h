@@ -1,0 +1,170 @@
+/*
+ * codegemm.h - C ABI of the MI355X (gfx950) CodeGEMM library.
+ *
+ * Computes the linear layer  y = x W^T  for a weight matrix W (N x K) that is
+ * stored codebook-quantized: every run of v consecutive weights along K is the
+ * sum of m centroid vectors, one from each of m codebooks of 256 fp16 centroids,
+ * selected by 8-bit codes, times one fp16 scale per output row
+ * (CodeGEMM paper, Section 2.2: vector length v, number of codebooks m, bits
+ * per code b = 8, normalisation group g = -1).
+ *
+ * The hot path never reconstructs W.  It builds a Psumbook (Section 3, Eq. 2)
+ *     P[b][c][j][i] = sum_{k<v} C[c][i][k] * x[b][v*j + k]
+ * in LDS, then gathers P by code and accumulates over j and c (Section 3,
+ * Step 3), and multiplies by the row scale.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers (HBM) unless marked "host".
+ *     The descriptor and plan structs are host structs passed by pointer.
+ *   - The caller owns every buffer.  The library allocates nothing, keeps no
+ *     global state and never synchronises: work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Inputs are read-only.  Outputs are fully overwritten.  Buffers must not
+ *     alias.  Every pointer must be 16-byte aligned.
+ *   - Return value: CODEGEMM_OK (0) or a negative codegemm_status.  No entry
+ *     point prints, throws or aborts.
+ *
+ * Canonical layouts (row-major, contiguous)
+ *     x          [B][K]        fp16
+ *     codes      [m][N][K/v]   uint8   (every value 0..255 is a valid centroid index)
+ *     codebooks  [m][256][v]   fp16
+ *     scales     [N]           fp16
+ *     y          [B][N]        fp16, or fp32 when CODEGEMM_FLAG_Y_FP32 is set
+ *     psumbook   [B][m][K/v][256] fp32
+ */
+#ifndef CODEGEMM_H
+#define CODEGEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum codegemm_status {
+    CODEGEMM_OK = 0,
+    CODEGEMM_INVALID_ARG = -1,        /* NULL pointer, non-positive size, K % v != 0, misaligned pointer */
+    CODEGEMM_UNSUPPORTED = -2,        /* v, m, b, g, batch or plan outside what the kernels implement   */
+    CODEGEMM_WORKSPACE_TOO_SMALL = -3,
+    CODEGEMM_LAUNCH_FAILED = -4       /* the HIP runtime rejected a launch or a memset                  */
+} codegemm_status;
+
+enum {
+    CODEGEMM_FLAG_Y_FP32 = 1          /* y is float[B][N] instead of fp16 */
+};
+
+/* Problem descriptor (host struct). */
+typedef struct codegemm_desc {
+    int32_t batch;          /* B, 1..32                                        */
+    int32_t in_features;    /* K, a positive multiple of vec_len               */
+    int32_t out_features;   /* N >= 1                                          */
+    int32_t vec_len;        /* v: 4 or 8                                       */
+    int32_t num_codebooks;  /* m: 1..4                                         */
+    int32_t code_bits;      /* b: must be 8 (Section 6, Limitations)           */
+    int32_t group_size;     /* g: must be -1 (one scale per output row)        */
+    int32_t flags;          /* CODEGEMM_FLAG_*                                 */
+} codegemm_desc;
+
+/*
+ * Launch plan of codegemm_gemm (host struct).  The paper's tile is t_h rows by
+ * t_w weights (Section 3); here t_w = slots * v and t_h = 512 * row_waves.
+ * One workgroup of row_waves * k_waves wavefronts owns one tile: it builds the
+ * tile's Psumbook (m * 256 * slots fp32 in LDS) once and every wavefront
+ * gathers from it.  `slots` also fixes the packed code layout, so codes packed
+ * under one value of `slots` can only be used with plans of the same `slots`.
+ */
+typedef struct codegemm_plan {
+    int32_t slots;          /* sub-vectors per K tile: 32 or 64; m*256*slots*4 bytes of LDS <= 160 KB */
+    int32_t row_waves;      /* wavefronts along N per workgroup (512 rows each): 1, 2, 4, 8           */
+    int32_t k_waves;        /* wavefronts sharing the same rows, splitting the tile's slots;          */
+                            /* slots / k_waves must be an integer <= 16; row_waves * k_waves <= 16    */
+    int32_t build;          /* Psumbook build: 0 = packed fp16 dot products on the vector ALU,        */
+                            /*                 1 = MFMA 32x32x8 fp16 tiles                            */
+    int32_t reserved[4];    /* must be zero */
+} codegemm_plan;
+
+/* Fills *plan with the library's choice for this problem.  Host only, no GPU work. */
+int codegemm_default_plan(const codegemm_desc *desc, codegemm_plan *plan);
+
+/* Bytes of `workspace` codegemm_gemm needs under `plan` (NULL plan = default plan).
+ * Returns 0 for an invalid descriptor or plan. */
+size_t codegemm_workspace_bytes(const codegemm_desc *desc, const codegemm_plan *plan);
+
+/* Bytes of the packed code buffer under `plan` (NULL = default).  0 if invalid. */
+size_t codegemm_packed_codes_bytes(const codegemm_desc *desc, const codegemm_plan *plan);
+
+/*
+ * Prepares a workspace for codegemm_gemm: zero-fills it.  Must be enqueued once
+ * after allocation, before the first codegemm_gemm that uses the workspace.
+ * Every codegemm_gemm call leaves the workspace ready for the next call on the
+ * same stream, so this is a one-time cost.  Two calls that use the same
+ * workspace concurrently (different streams) race.
+ */
+int codegemm_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Re-orders canonical codes [m][N][K/v] into the packed streaming layout the
+ * gather kernel reads (offline, once per weight matrix), and back.
+ *
+ * Packed layout.  Let S = plan.slots, J = K / v, NRB = ceil(N / 512),
+ * NKT = ceil(J / S).  The buffer is an array [NRB][NKT][S][part][64][bytes]
+ * where the step index t runs over 0..S-1, the lane index l over 0..63, and the
+ * 8*m bytes a lane reads per step are split into parts of 16 bytes (two
+ * codebooks) plus, for odd m, a last part of 8 bytes (one codebook).  Within a
+ * part, byte 8*(c - c0) + r holds, for codebook c and r = 0..7,
+ *     codes[c][512*rb + 64*r + l][S*kt + ((t + l) mod S)]
+ * or 0 when that row or sub-vector lies outside the matrix.  The rotation by
+ * the lane index makes the 64 lanes of a wavefront read 64 different slots of
+ * the Psumbook in every step, which keeps the data-dependent LDS gathers free
+ * of bank conflicts whatever the code values are.  Bytes are stored as such,
+ * so a 32-bit word read from the buffer holds byte q in bits 8q..8q+7.
+ *
+ * Both calls are bit-exact: unpack(pack(codes)) == codes.
+ */
+int codegemm_pack_codes(const codegemm_desc *desc, const codegemm_plan *plan,
+                        const uint8_t *codes, uint8_t *packed, void *stream);
+int codegemm_unpack_codes(const codegemm_desc *desc, const codegemm_plan *plan,
+                          const uint8_t *packed, uint8_t *codes, void *stream);
+
+/*
+ * Section 3, Eq. 2, for the whole of K: psumbook[b][c][j][i] (fp32), from
+ * x [B][K] fp16 and codebooks [m][256][v] fp16.  fp16 products are exact in
+ * fp32 and are accumulated in fp32.  use_mfma != 0 computes the contraction on
+ * the matrix cores (the (m*256) x (B*K/v) x v product), 0 on the vector ALU.
+ */
+int codegemm_psumbook_build(const codegemm_desc *desc, const void *x, const void *codebooks,
+                            float *psumbook, int use_mfma, void *stream);
+
+/*
+ * The hot path (Section 3, Steps 1-3, then de-normalisation by the row scale):
+ *     y[b][n] = scales[n] * sum_{c<m} sum_{j<K/v} P[b][c][j][ codes[c][n][j] ].
+ * `packed_codes` is the output of codegemm_pack_codes under the same plan.slots.
+ * fp16 inputs, fp32 Psumbook and accumulation, y rounded to nearest-even fp16
+ * (or stored as fp32 under CODEGEMM_FLAG_Y_FP32).  The partial sums of the
+ * K tiles are combined in a fixed order, so results are bit-reproducible.
+ * `workspace` holds at least codegemm_workspace_bytes() bytes and has been
+ * through codegemm_workspace_init once.  plan == NULL uses the default plan.
+ */
+int codegemm_gemm(const codegemm_desc *desc, const codegemm_plan *plan,
+                  const void *x, const uint8_t *packed_codes, const void *codebooks,
+                  const void *scales, void *y, void *workspace, size_t workspace_bytes,
+                  void *stream);
+
+/*
+ * Dequantization-based comparator (Section 2.3: the whole codebook sits in LDS,
+ * each code fetches its centroid vector, which is multiplied with the matching
+ * activations; O(N*B*K) multiply-adds).  Same result as codegemm_gemm up to
+ * fp32 summation order.  `codes` is the canonical [m][N][K/v] array.  Needs no
+ * workspace.
+ */
+int codegemm_dequant_gemm(const codegemm_desc *desc, const void *x, const uint8_t *codes,
+                          const void *codebooks, const void *scales, void *y, void *stream);
+
+/* Static, NUL-terminated description of a status code.  Host only. */
+const char *codegemm_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CODEGEMM_H */

@@ -1,0 +1,166 @@
+"""ctypes binding of include/codegemm.h.  Same names as the C entry points.
+
+Tensor arguments are anything with `.data_ptr()` (torch tensors on the GPU) or
+plain integer device addresses.  `stream` is a HIP stream handle as an integer
+(e.g. `torch.cuda.current_stream().cuda_stream`), 0 for the default stream.
+Functions raise CodegemmError on a non-zero status.  There is no fallback: if
+the library has not been built, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libcodegemm.so")
+_lib: Optional[ctypes.CDLL] = None
+
+FLAG_Y_FP32 = 1
+
+EXPORTS = [
+    "codegemm_default_plan", "codegemm_workspace_bytes", "codegemm_packed_codes_bytes",
+    "codegemm_workspace_init", "codegemm_pack_codes", "codegemm_unpack_codes",
+    "codegemm_psumbook_build", "codegemm_gemm", "codegemm_dequant_gemm", "codegemm_status_string",
+]
+
+
+class CodegemmError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {codegemm_status_string(status)} ({status})")
+
+
+class Desc(ctypes.Structure):
+    """codegemm_desc"""
+    _fields_ = [("batch", ctypes.c_int32), ("in_features", ctypes.c_int32), ("out_features", ctypes.c_int32),
+                ("vec_len", ctypes.c_int32), ("num_codebooks", ctypes.c_int32), ("code_bits", ctypes.c_int32),
+                ("group_size", ctypes.c_int32), ("flags", ctypes.c_int32)]
+
+    @classmethod
+    def make(cls, B: int, K: int, N: int, v: int, m: int, y_fp32: bool = False, b: int = 8, g: int = -1):
+        return cls(B, K, N, v, m, b, g, FLAG_Y_FP32 if y_fp32 else 0)
+
+
+class Plan(ctypes.Structure):
+    """codegemm_plan"""
+    _fields_ = [("slots", ctypes.c_int32), ("row_waves", ctypes.c_int32), ("k_waves", ctypes.c_int32),
+                ("build", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4)]
+
+    @classmethod
+    def make(cls, slots: int, row_waves: int, k_waves: int, build: int = 0):
+        return cls(slots, row_waves, k_waves, build, (ctypes.c_int32 * 4)(0, 0, 0, 0))
+
+    def __repr__(self):
+        return f"Plan(slots={self.slots}, row_waves={self.row_waves}, k_waves={self.k_waves}, build={self.build})"
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Loads libcodegemm.so; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(or python paper_2512_17970_amd/build.py) first; there is no CPU fallback")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    dp, pp = ctypes.POINTER(Desc), ctypes.POINTER(Plan)
+    lib.codegemm_default_plan.argtypes = [dp, pp]
+    lib.codegemm_default_plan.restype = i
+    lib.codegemm_workspace_bytes.argtypes = [dp, pp]
+    lib.codegemm_workspace_bytes.restype = sz
+    lib.codegemm_packed_codes_bytes.argtypes = [dp, pp]
+    lib.codegemm_packed_codes_bytes.restype = sz
+    lib.codegemm_workspace_init.argtypes = [vp, sz, vp]
+    lib.codegemm_workspace_init.restype = i
+    lib.codegemm_pack_codes.argtypes = [dp, pp, vp, vp, vp]
+    lib.codegemm_pack_codes.restype = i
+    lib.codegemm_unpack_codes.argtypes = [dp, pp, vp, vp, vp]
+    lib.codegemm_unpack_codes.restype = i
+    lib.codegemm_psumbook_build.argtypes = [dp, vp, vp, vp, i, vp]
+    lib.codegemm_psumbook_build.restype = i
+    lib.codegemm_gemm.argtypes = [dp, pp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.codegemm_gemm.restype = i
+    lib.codegemm_dequant_gemm.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+    lib.codegemm_dequant_gemm.restype = i
+    lib.codegemm_status_string.argtypes = [i]
+    lib.codegemm_status_string.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> ctypes.c_void_p:
+    if t is None:
+        return ctypes.c_void_p(0)
+    if hasattr(t, "data_ptr"):
+        return ctypes.c_void_p(t.data_ptr())
+    return ctypes.c_void_p(int(t))
+
+
+def _plan(plan: Optional[Plan]):
+    return ctypes.byref(plan) if plan is not None else None
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise CodegemmError(status, where)
+
+
+def codegemm_status_string(status: int) -> str:
+    return load().codegemm_status_string(int(status)).decode()
+
+
+def codegemm_default_plan(desc: Desc) -> Plan:
+    plan = Plan()
+    _check(load().codegemm_default_plan(ctypes.byref(desc), ctypes.byref(plan)), "codegemm_default_plan")
+    return plan
+
+
+def codegemm_workspace_bytes(desc: Desc, plan: Optional[Plan] = None) -> int:
+    return int(load().codegemm_workspace_bytes(ctypes.byref(desc), _plan(plan)))
+
+
+def codegemm_packed_codes_bytes(desc: Desc, plan: Optional[Plan] = None) -> int:
+    return int(load().codegemm_packed_codes_bytes(ctypes.byref(desc), _plan(plan)))
+
+
+def codegemm_workspace_init(workspace, workspace_bytes: int, stream: int = 0) -> None:
+    _check(load().codegemm_workspace_init(_ptr(workspace), workspace_bytes, ctypes.c_void_p(stream)),
+           "codegemm_workspace_init")
+
+
+def codegemm_pack_codes(desc: Desc, plan: Optional[Plan], codes, packed, stream: int = 0) -> None:
+    _check(load().codegemm_pack_codes(ctypes.byref(desc), _plan(plan), _ptr(codes), _ptr(packed),
+                                      ctypes.c_void_p(stream)), "codegemm_pack_codes")
+
+
+def codegemm_unpack_codes(desc: Desc, plan: Optional[Plan], packed, codes, stream: int = 0) -> None:
+    _check(load().codegemm_unpack_codes(ctypes.byref(desc), _plan(plan), _ptr(packed), _ptr(codes),
+                                        ctypes.c_void_p(stream)), "codegemm_unpack_codes")
+
+
+def codegemm_psumbook_build(desc: Desc, x, codebooks, psumbook, use_mfma: bool = False, stream: int = 0) -> None:
+    _check(load().codegemm_psumbook_build(ctypes.byref(desc), _ptr(x), _ptr(codebooks), _ptr(psumbook),
+                                          1 if use_mfma else 0, ctypes.c_void_p(stream)), "codegemm_psumbook_build")
+
+
+def codegemm_gemm(desc: Desc, plan: Optional[Plan], x, packed_codes, codebooks, scales, y,
+                  workspace, workspace_bytes: int, stream: int = 0) -> None:
+    _check(load().codegemm_gemm(ctypes.byref(desc), _plan(plan), _ptr(x), _ptr(packed_codes), _ptr(codebooks),
+                                _ptr(scales), _ptr(y), _ptr(workspace), workspace_bytes,
+                                ctypes.c_void_p(stream)), "codegemm_gemm")
+
+
+def codegemm_dequant_gemm(desc: Desc, x, codes, codebooks, scales, y, stream: int = 0) -> None:
+    _check(load().codegemm_dequant_gemm(ctypes.byref(desc), _ptr(x), _ptr(codes), _ptr(codebooks), _ptr(scales),
+                                        _ptr(y), ctypes.c_void_p(stream)), "codegemm_dequant_gemm")
+
+
+def compressed_bytes(B: int, K: int, N: int, v: int, m: int) -> int:
+    """Bytes the method must move per call: codes + codebooks + scales + x + y (fp16 y)."""
+    return m * N * (K // v) + m * 256 * v * 2 + 2 * N + 2 * B * K + 2 * B * N

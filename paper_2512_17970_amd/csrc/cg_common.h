@@ -1,0 +1,65 @@
+// Internal definitions shared by the translation units of libcodegemm (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "codegemm.h"
+
+namespace cg {
+
+constexpr int kCentroids = 256;     // 2^b with b = 8
+constexpr int kWave = 64;           // CDNA wavefront width
+constexpr int kRowsPerLane = 8;     // output rows owned by one lane of the gather kernel
+constexpr int kBlockRows = kWave * kRowsPerLane;   // 512 rows per wavefront
+constexpr int kMaxLds = 160 * 1024; // LDS per workgroup on gfx950
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+// Derived sizes of one problem under one plan.
+struct Geometry {
+    int B, K, N, v, m, J;
+    int S;          // slots per K tile
+    int RW, JW;     // wavefronts per workgroup along N and along the tile's slots
+    int NSTEP;      // S / JW steps per wavefront
+    int NRB;        // ceil(N / 512) row blocks
+    int NKT;        // ceil(J / S) K tiles
+    int NRT;        // ceil(NRB / RW) row tiles
+    int Npad;       // NRB * 512
+    int build;      // 0 VALU, 1 MFMA
+    bool y_fp32;
+};
+
+__host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Bytes one lane reads per step, and per-step bytes of a whole wavefront.
+__host__ __device__ inline int step_bytes(int m) { return kWave * kRowsPerLane * m; }
+
+// Offset of the packed byte that holds codes[c][n][j]  (see codegemm.h, packed layout).
+__host__ __device__ inline size_t packed_offset(int c, int n, int j, int m, int S, int NKT)
+{
+    const int rb = n / kBlockRows;
+    const int r = (n % kBlockRows) / kWave;
+    const int l = n % kWave;
+    const int kt = j / S;
+    const int slot = j % S;
+    const int t = (slot - l) & (S - 1);
+    const int part = c >> 1;
+    const int part_bytes = (2 * part + 1 == m) ? 8 : 16;   // last part of an odd m holds one codebook
+    size_t off = (((size_t)rb * NKT + kt) * S + t) * (size_t)step_bytes(m);
+    off += (size_t)part * 16 * kWave + (size_t)l * part_bytes + (c & 1) * 8 + r;
+    return off;
+}
+
+int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g);   // status
+size_t workspace_counter_bytes(const Geometry& g);
+size_t lds_bytes_gemm(const Geometry& g);
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+}  // namespace cg

@@ -1,0 +1,93 @@
+// Code re-ordering between the canonical [m][N][K/v] array and the packed
+// streaming layout of the gather kernel, and the workspace fill.
+#include "cg_common.h"
+
+namespace cg {
+
+// One thread per (codebook, padded row, padded sub-vector): every packed byte is
+// written exactly once, positions outside the matrix get code 0.
+__global__ void __launch_bounds__(256)
+pack_kernel(const uint8_t* __restrict__ codes, uint8_t* __restrict__ packed,
+            int N, int J, int m, int S, int NKT, int Npad, int Jpad)
+{
+    const size_t total = (size_t)m * Npad * Jpad;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (size_t)gridDim.x * blockDim.x) {
+        const int j = (int)(idx % Jpad);
+        const int n = (int)((idx / Jpad) % Npad);
+        const int c = (int)(idx / ((size_t)Jpad * Npad));
+        uint8_t code = 0;
+        if (n < N && j < J) code = codes[((size_t)c * N + n) * J + j];
+        packed[packed_offset(c, n, j, m, S, NKT)] = code;
+    }
+}
+
+__global__ void __launch_bounds__(256)
+unpack_kernel(const uint8_t* __restrict__ packed, uint8_t* __restrict__ codes,
+              int N, int J, int m, int S, int NKT)
+{
+    const size_t total = (size_t)m * N * J;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (size_t)gridDim.x * blockDim.x) {
+        const int j = (int)(idx % J);
+        const int n = (int)((idx / J) % N);
+        const int c = (int)(idx / ((size_t)J * N));
+        codes[idx] = packed[packed_offset(c, n, j, m, S, NKT)];
+    }
+}
+
+// A plain fill kernel rather than a memset node, so the call can be captured
+// in a HIP graph.
+__global__ void __launch_bounds__(256) zero_kernel(uint32_t* p, size_t words)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < words;
+         i += (size_t)gridDim.x * blockDim.x)
+        p[i] = 0u;
+}
+
+static int grid_for(size_t total)
+{
+    size_t blocks = (total + 255) / 256;
+    return (int)(blocks > 8192 ? 8192 : (blocks ? blocks : 1));
+}
+
+}  // namespace cg
+
+using namespace cg;
+
+extern "C" int codegemm_pack_codes(const codegemm_desc* desc, const codegemm_plan* plan,
+                                   const uint8_t* codes, uint8_t* packed, void* stream)
+{
+    Geometry g;
+    int st = make_geometry(desc, plan, &g);
+    if (st) return st;
+    if (!codes || !packed || misaligned(codes) || misaligned(packed)) return CODEGEMM_INVALID_ARG;
+    const int Jpad = g.NKT * g.S;
+    const size_t total = (size_t)g.m * g.Npad * Jpad;
+    hipLaunchKernelGGL(pack_kernel, dim3(grid_for(total)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       codes, packed, g.N, g.J, g.m, g.S, g.NKT, g.Npad, Jpad);
+    return hipGetLastError() == hipSuccess ? CODEGEMM_OK : CODEGEMM_LAUNCH_FAILED;
+}
+
+extern "C" int codegemm_unpack_codes(const codegemm_desc* desc, const codegemm_plan* plan,
+                                     const uint8_t* packed, uint8_t* codes, void* stream)
+{
+    Geometry g;
+    int st = make_geometry(desc, plan, &g);
+    if (st) return st;
+    if (!codes || !packed || misaligned(codes) || misaligned(packed)) return CODEGEMM_INVALID_ARG;
+    const size_t total = (size_t)g.m * g.N * g.J;
+    hipLaunchKernelGGL(unpack_kernel, dim3(grid_for(total)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       packed, codes, g.N, g.J, g.m, g.S, g.NKT);
+    return hipGetLastError() == hipSuccess ? CODEGEMM_OK : CODEGEMM_LAUNCH_FAILED;
+}
+
+extern "C" int codegemm_workspace_init(void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!workspace || workspace_bytes == 0 || (workspace_bytes & 3) || misaligned(workspace))
+        return CODEGEMM_INVALID_ARG;
+    const size_t words = workspace_bytes / 4;
+    hipLaunchKernelGGL(zero_kernel, dim3(grid_for(words)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<uint32_t*>(workspace), words);
+    return hipGetLastError() == hipSuccess ? CODEGEMM_OK : CODEGEMM_LAUNCH_FAILED;
+}

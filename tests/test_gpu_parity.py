@@ -1,0 +1,159 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from oracle.pack_layout import pack_reference
+
+pytestmark = pytest.mark.gpu
+
+cg = pytest.importorskip("paper_2512_17970_amd")
+from gpu_util import DeviceLayer, check_against_oracle, dev, stream  # noqa: E402
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def run_case(case, plan=None, y_fp32=False, dequant=True):
+    say(f"[case] {case.name} seed={case.seed} plan={plan} y_fp32={y_fp32}")
+    inp = synth.generate(case)
+    y_ref, T = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+    layer = DeviceLayer(inp, plan=plan, y_fp32=y_fp32)
+    y = layer.gemm()
+    torch.cuda.synchronize()
+    rel = check_against_oracle(y.cpu().numpy(), y_ref, T, f"codegemm_gemm {case.name}")
+    # second call on the same workspace: the ticket counters must have been reset
+    y2 = layer.gemm()
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2), "second call differs (workspace not left ready / not deterministic)"
+    if dequant:
+        yd = layer.dequant()
+        torch.cuda.synchronize()
+        check_against_oracle(yd.cpu().numpy(), y_ref, T, f"codegemm_dequant_gemm {case.name}")
+    return rel
+
+
+SMALL = [
+    # K, N, v, m, B : several tiles, ragged tails in N (not a multiple of 512 or 64) and in K (not a multiple of S*v)
+    (512, 512, 8, 1, 1), (512, 512, 8, 2, 1), (1032, 1000, 8, 2, 1), (520, 63, 8, 2, 1), (8, 1, 8, 1, 1),
+    (4 * 131, 700, 4, 1, 1), (2048, 1537, 4, 1, 1), (776, 515, 8, 3, 1), (264, 1025, 4, 4, 1),
+    (1024, 600, 8, 2, 3), (4 * 67, 130, 4, 2, 5), (1536, 2100, 8, 1, 2),
+]
+
+
+@pytest.mark.parametrize("K,N,v,m,B", SMALL)
+def test_small_shapes_default_plan(K, N, v, m, B):
+    run_case(synth.custom_case(K, N, v, m, B, seed=4242 + K + N))
+
+
+@pytest.mark.parametrize("y_fp32", [False, True])
+def test_tiny_config(y_fp32):
+    run_case(synth.workloads()[1][0], y_fp32=y_fp32)
+
+
+PLANS = [(64, 1, 16), (64, 1, 8), (64, 1, 4), (64, 2, 8), (64, 2, 4), (64, 4, 4),
+         (32, 1, 8), (32, 1, 4), (32, 1, 2), (32, 2, 8), (32, 4, 4), (32, 8, 2), (32, 2, 2)]
+
+
+@pytest.mark.parametrize("slots,rw,jw", PLANS)
+@pytest.mark.parametrize("v,m", [(8, 2), (4, 1)])
+def test_every_plan_shape(slots, rw, jw, v, m):
+    case = synth.custom_case(v * 200, 1300, v, m, 1, seed=99)
+    run_case(case, plan=cg.Plan.make(slots, rw, jw), dequant=False)
+
+
+def test_pack_matches_documented_layout_and_roundtrips():
+    for (K, N, v, m) in [(8 * 100, 700, 8, 2), (4 * 77, 513, 4, 1), (8 * 40, 64, 8, 3), (8 * 33, 1030, 8, 4)]:
+        case = synth.custom_case(K, N, v, m, 1, seed=7)
+        inp = synth.generate(case)
+        desc = cg.Desc.make(1, K, N, v, m)
+        for slots in ([32, 64] if m <= 2 else [32]):
+            say(f"[pack] {case.name} slots={slots}")
+            plan = cg.Plan.make(slots, 1, slots // 4 if slots // 4 <= 16 else 16)
+            nbytes = cg.codegemm_packed_codes_bytes(desc, plan)
+            want = pack_reference(inp.codes, slots)
+            assert nbytes == want.size
+            codes_d = dev(inp.codes)
+            packed = torch.full((nbytes,), 0xAB, dtype=torch.uint8, device="cuda")
+            cg.codegemm_pack_codes(desc, plan, codes_d, packed, stream())
+            back = torch.full_like(codes_d, 0xCD)
+            cg.codegemm_unpack_codes(desc, plan, packed, back, stream())
+            torch.cuda.synchronize()
+            assert np.array_equal(packed.cpu().numpy(), want)
+            assert torch.equal(back, codes_d)
+
+
+@pytest.mark.parametrize("use_mfma", [False, True])
+@pytest.mark.parametrize("K,v,m,B", [(512, 8, 2, 1), (4 * 67, 4, 1, 3), (8 * 45, 8, 3, 9), (1024, 4, 4, 2)])
+def test_psumbook_build_eq2(K, v, m, B, use_mfma):
+    case = synth.custom_case(K, 8, v, m, B, seed=5)
+    say(f"[psumbook] {case.name} mfma={use_mfma}")
+    inp = synth.generate(case)
+    P_ref = oracle.psumbook(inp.x, inp.codebooks)
+    desc = cg.Desc.make(B, K, 8, v, m)
+    P = torch.full((B, m, K // v, 256), float("nan"), dtype=torch.float32, device="cuda")
+    cg.codegemm_psumbook_build(desc, dev(inp.x), dev(inp.codebooks), P, use_mfma, stream())
+    torch.cuda.synchronize()
+    got = P.cpu().numpy().astype(np.float64)
+    # fp16 products are exact in fp32; v-1 fp32 additions: error <= v * 2^-24 * sum|terms|
+    bound = v * 2.0 ** -24 * np.einsum("bjk,cik->bcji", np.abs(inp.x.astype(np.float64)).reshape(B, -1, v),
+                                       np.abs(inp.codebooks.astype(np.float64)))
+    assert np.all(np.abs(got - P_ref) <= bound + 1e-30)
+
+
+def test_psumbook_one_hot_is_exact_copy_of_x():
+    v, K, B = 8, 8 * 96, 2
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((B, K)).astype(np.float16)
+    cb = np.zeros((1, 256, v), np.float16)
+    cb[0, np.arange(256), np.arange(256) % v] = 1.0
+    desc = cg.Desc.make(B, K, 8, v, 1)
+    for use_mfma in (False, True):
+        P = torch.empty((B, 1, K // v, 256), dtype=torch.float32, device="cuda")
+        cg.codegemm_psumbook_build(desc, dev(x), dev(cb), P, use_mfma, stream())
+        torch.cuda.synchronize()
+        want = x.astype(np.float32).reshape(B, K // v, v)[:, :, np.arange(256) % v]
+        assert np.array_equal(P.cpu().numpy()[:, 0], want)
+
+
+@pytest.mark.parametrize("lo", [-1.0, 0.0])
+def test_sign_codebook_bit_exact(lo):
+    """+-1 / {0,1} codebooks with small integer x: every partial sum is an exactly
+    representable integer, so the fp32 result must equal the oracle bit for bit
+    whatever the summation order."""
+    v, K, N, B = 8, 8192, 2100, 2
+    rng = np.random.default_rng(17)
+    i = np.arange(256)[:, None]
+    cb = np.where((i >> np.arange(v)[None, :]) & 1, 1.0, lo).astype(np.float16)[None]
+    case = synth.custom_case(K, N, v, 1, B, seed=1)
+    inp = synth.generate(case)
+    inp.codebooks = cb
+    inp.x = rng.integers(-8, 9, (B, K)).astype(np.float16)
+    inp.scales = np.ones(N, np.float16)
+    y_ref, _ = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+    layer = DeviceLayer(inp, y_fp32=True)
+    y = layer.gemm()
+    yd = layer.dequant()
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy().astype(np.float64), y_ref)
+    assert np.array_equal(yd.cpu().numpy().astype(np.float64), y_ref)
+
+
+def test_error_paths():
+    d = cg.Desc.make(1, 512, 512, 8, 1)
+    t = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    with pytest.raises(cg.CodegemmError):
+        cg.codegemm_gemm(cg.Desc.make(1, 510, 512, 8, 1), None, t, t, t, t, t, t, 1 << 20)       # K % v
+    with pytest.raises(cg.CodegemmError):
+        cg.codegemm_gemm(cg.Desc.make(1, 512, 512, 16, 1), None, t, t, t, t, t, t, 1 << 20)      # v
+    with pytest.raises(cg.CodegemmError):
+        cg.codegemm_gemm(d, None, t, t, t, t, t, t, 16)                                          # workspace
+    with pytest.raises(cg.CodegemmError):
+        cg.codegemm_gemm(d, None, None, t, t, t, t, t, 1 << 20)                                  # NULL
+    with pytest.raises(cg.CodegemmError):
+        cg.codegemm_gemm(d, cg.Plan.make(48, 1, 4), t, t, t, t, t, t, 1 << 20)                   # plan
+    with pytest.raises(cg.CodegemmError):
+        cg.codegemm_gemm(d, None, t[1:], t, t, t, t, t, 1 << 20)                                 # alignment
