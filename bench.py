@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Benchmark of the CodeGEMM hot path on one MI355X.
+
+A "step" is one call of codegemm_gemm for each of the four Llama-3-70B linear
+layer shapes (8192->8192, 8192->1024, 8192->28672, 28672->8192) at batch 1,
+2-bit (v=8, m=2), on synthetic seeded inputs already resident in HBM.  Every
+step reads a different copy of the packed codes (the copies of one shape add up
+to >= 1 GiB), so the weights come from HBM and not from the last-level cache.
+
+Prints ONE JSON line: the metric is effective HBM bandwidth on compressed bytes
+(codes + codebooks + scales + x + y per call, summed over the step, divided by
+the step time), with a `roofline` object for the gather kernel and a
+`cpu_baseline` object (the CPU oracle timed on this host).  Per-shape detail
+(cold and cache-warm us/call, the dequantization comparator, the ratio) goes to
+stderr and, when the directory exists, to gpurun_out/bench_detail.json.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+COLD_BYTES = 1 << 30            # rotating working set per shape
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c3", help="c2 | c3 | c5 | a single case name from synth.workloads()")
+    ap.add_argument("--launch", default="graph", choices=["graph", "direct"],
+                    help="graph: the K timed steps are one captured HIP graph (no host launch cost); direct: plain launches")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-detail", action="store_true", help="skip the per-shape cold/warm/dequant table")
+    ap.add_argument("--plan", default="", help="override plan for every shape: slots,waves,k_splits[,batch_group]")
+    return ap.parse_args()
+
+
+class Layer:
+    """One quantized layer on the GPU with R rotating copies of its packed codes."""
+
+    def __init__(self, cg, torch, synth, case, plan_override, copies_bytes=COLD_BYTES):
+        self.cg, self.torch, self.case = cg, torch, case
+        inp = synth.generate(case)
+        self.inp = inp
+        self.desc = cg.Desc.make(case.B, case.K, case.N, case.v, case.m)
+        self.plan = plan_override if plan_override is not None else cg.codegemm_default_plan(self.desc)
+        dev = lambda a: torch.from_numpy(a).cuda()
+        self.x, self.codes = dev(inp.x), dev(inp.codes)
+        self.codebooks, self.scales = dev(inp.codebooks), dev(inp.scales)
+        self.y = torch.empty((case.B, case.N), dtype=torch.float16, device="cuda")
+        nbytes = cg.codegemm_packed_codes_bytes(self.desc, self.plan)
+        self.R = max(2, -(-copies_bytes // nbytes))
+        self.packed = torch.empty((self.R, nbytes), dtype=torch.uint8, device="cuda")
+        s = torch.cuda.current_stream().cuda_stream
+        cg.codegemm_pack_codes(self.desc, self.plan, self.codes, self.packed[0], s)
+        for r in range(1, self.R):
+            self.packed[r].copy_(self.packed[0])
+        self.ws_bytes = cg.codegemm_workspace_bytes(self.desc, self.plan)
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device="cuda")
+        cg.codegemm_workspace_init(self.ws, self.ws_bytes, s)
+        self.bytes = cg.compressed_bytes(case.B, case.K, case.N, case.v, case.m)
+        self.i = 0
+
+    def gemm(self, copy=None):
+        r = self.i % self.R if copy is None else copy
+        self.i += 1
+        self.cg.codegemm_gemm(self.desc, self.plan, self.x, self.packed[r], self.codebooks, self.scales, self.y,
+                              self.ws, self.ws_bytes, self.torch.cuda.current_stream().cuda_stream)
+
+    def dequant(self):
+        self.cg.codegemm_dequant_gemm(self.desc, self.x, self.codes, self.codebooks, self.scales, self.y,
+                                      self.torch.cuda.current_stream().cuda_stream)
+
+
+def time_region(torch, fn, reps):
+    """Device time of `reps` back-to-back calls of fn() between two events on the launch stream (ms)."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1)
+
+
+def graph_of(torch, fn, reps):
+    """Captures `reps` calls of fn() (kernel launches only) into one HIP graph."""
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(reps):
+                fn()
+    torch.cuda.current_stream().wait_stream(side)
+    return g
+
+
+def per_shape_detail(torch, layers, launch):
+    rows = []
+    for L in layers:
+        row = {"case": L.case.name, "plan": repr(L.plan), "compressed_bytes": L.bytes, "copies": L.R}
+        for label, fn in (("cold", lambda: L.gemm()), ("warm", lambda: L.gemm(0))):
+            n = 200
+            for _ in range(20):
+                fn()
+            if launch == "graph":
+                L.i = 0
+                g = graph_of(torch, fn, n)
+                ts = [time_region(torch, g.replay, 1) * 1e3 / n for _ in range(5)]
+            else:
+                ts = [time_region(torch, fn, n) * 1e3 / n for _ in range(5)]
+            row[f"us_{label}_min"], row[f"us_{label}_median"] = min(ts), statistics.median(ts)
+        dq_n = 20
+        for _ in range(3):
+            L.dequant()
+        ts = [time_region(torch, L.dequant, dq_n) * 1e3 / dq_n for _ in range(3)]
+        row["us_dequant_min"] = min(ts)
+        row["GBps_cold"] = L.bytes / row["us_cold_min"] * 1e-3
+        row["frac_of_peak_cold"] = row["GBps_cold"] / HBM_PEAK_GBPS
+        row["GBps_warm"] = L.bytes / row["us_warm_min"] * 1e-3
+        row["dequant_over_codegemm"] = row["us_dequant_min"] / row["us_cold_min"]
+        rows.append(row)
+        log(f"  {row['case']:28s} {row['plan']}: cold {row['us_cold_min']:.2f} us ({row['GBps_cold']:.0f} GB/s, "
+            f"{100 * row['frac_of_peak_cold']:.1f}% of peak)  warm {row['us_warm_min']:.2f} us  "
+            f"dequant {row['us_dequant_min']:.2f} us ({row['dequant_over_codegemm']:.1f}x)")
+    return rows
+
+
+def cpu_baseline(cases, synth, budget_s=12.0):
+    """The CPU oracle, as it stands, on this host's cores, on a bounded sample."""
+    import oracle
+    inputs = [synth.generate(c) for c in cases]
+    total_bytes = 0
+    total_s = 0.0
+    detail = []
+    for c, inp in zip(cases, inputs):
+        best = float("inf")
+        t_start = time.perf_counter()
+        reps = 0
+        while reps < 3 or (time.perf_counter() - t_start < budget_s / len(cases) and reps < 20):
+            t0 = time.perf_counter()
+            oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+            best = min(best, time.perf_counter() - t0)
+            reps += 1
+        nbytes = c.m * c.N * c.J + c.m * 256 * c.v * 2 + 2 * c.N + 2 * c.B * c.K + 2 * c.B * c.N
+        total_bytes += nbytes
+        total_s += best
+        detail.append({"case": c.name, "ms": best * 1e3, "reps": reps})
+    return {"value": total_bytes / total_s * 1e-9, "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "one oracle.gemm call per shape of the step (fp64 dequantize-then-multiply), best of >=3 each",
+            "ms_per_step": total_s * 1e3, "detail": detail}
+
+
+def read_traffic():
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "gemm_kernel_c3_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch="):
+                return float(line.split("=", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only; --gpus N with N > 1 is not supported "
+              "(the path would shard by output rows without any exchange; see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import synth
+    import paper_2512_17970_amd as cg
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    cg.load()
+    wl = synth.workloads()
+    key = args.workload.lower()
+    if key in ("c2", "c3", "c5"):
+        cases = wl[int(key[1])]
+    else:
+        cases = [synth.find_case(args.workload)]
+    plan_override = None
+    if args.plan:
+        plan_override = cg.Plan.make(*[int(t) for t in args.plan.split(",")])
+    log(f"device: {torch.cuda.get_device_name(0)}; workload {key}: {[c.name for c in cases]}")
+    layers = [Layer(cg, torch, synth, c, plan_override) for c in cases]
+    torch.cuda.synchronize()
+
+    def step():
+        for L in layers:
+            L.gemm()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if args.launch == "graph":
+        g = graph_of(torch, step, args.steps)
+        g.replay()                      # untimed: first replay uploads the graph
+        ms = time_region(torch, g.replay, 1)
+    else:
+        ms = time_region(torch, step, args.steps)
+    ms_per_step = ms / args.steps
+    step_bytes = sum(L.bytes for L in layers)
+    launches = len(layers) * args.steps
+    value = step_bytes / (ms_per_step * 1e-3) * 1e-9
+    us_per_launch = ms * 1e3 / launches
+    roofline = {"bound": "hbm", "achieved": value, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": value / HBM_PEAK_GBPS, "traffic": read_traffic(),
+                "kernel": "cg::gemm_kernel", "avg_launch_us": us_per_launch,
+                "algorithmic_bytes_per_launch": step_bytes / len(layers)}
+    out = {
+        "metric": "effective HBM GB/s on compressed bytes, Llama-3-70B layer shapes, bs=1, 2-bit (us/call in config)",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 in, f32 accumulate, u8 codes", "data": "synthetic",
+        "config": {"workload": f"{key}: " + ", ".join(c.name for c in cases),
+                   "calls_per_step": len(layers), "us_per_step": ms_per_step * 1e3, "launch": args.launch,
+                   "cold_copies_bytes_per_shape": COLD_BYTES},
+        "roofline": roofline,
+    }
+    detail = None
+    if not args.no_detail:
+        log("per-shape (min of 5 x 200 calls):")
+        detail = per_shape_detail(torch, layers, args.launch)
+        out["config"]["us_per_call_cold"] = {r["case"]: round(r["us_cold_min"], 3) for r in detail}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cases, synth)
+        log(f"cpu oracle: {out['cpu_baseline']['ms_per_step']:.1f} ms per step on {out['cpu_baseline']['cores']} threads")
+    else:
+        out["cpu_baseline"] = None
+    if detail is not None and os.path.isdir(os.path.join(ROOT, "gpurun_out")):
+        with open(os.path.join(ROOT, "gpurun_out", "bench_detail.json"), "w") as f:
+            json.dump({"summary": out, "per_shape": detail}, f, indent=1)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

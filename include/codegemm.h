@@ -68,19 +68,21 @@ typedef struct codegemm_desc {
 
 /*
  * Launch plan of codegemm_gemm (host struct).  The paper's tile is t_h rows by
- * t_w weights (Section 3); here t_w = slots * v and t_h = 512 * row_waves.
- * One workgroup of row_waves * k_waves wavefronts owns one tile: it builds the
- * tile's Psumbook (m * 256 * slots fp32 in LDS) once and every wavefront
- * gathers from it.  `slots` also fixes the packed code layout, so codes packed
- * under one value of `slots` can only be used with plans of the same `slots`.
+ * t_w weights (Section 3); here one "unit" is 512 rows by slots * v weights, and
+ * one workgroup streams through a contiguous run of units of one 512-row block
+ * (all of K when k_splits = 1), rebuilding the Psumbook (m * 256 * slots fp32
+ * in LDS, double-buffered when two copies fit in 128 KB) once per unit.
+ * `slots` also fixes the packed code layout: codes packed under one value of
+ * `slots` can only be used with plans of the same `slots`.
  */
 typedef struct codegemm_plan {
-    int32_t slots;          /* sub-vectors per K tile: 32 or 64; m*256*slots*4 bytes of LDS <= 160 KB */
-    int32_t row_waves;      /* wavefronts along N per workgroup (512 rows each): 1, 2, 4, 8           */
-    int32_t k_waves;        /* wavefronts sharing the same rows, splitting the tile's slots;          */
-                            /* slots / k_waves must be an integer <= 16; row_waves * k_waves <= 16    */
-    int32_t build;          /* Psumbook build: 0 = packed fp16 dot products on the vector ALU,        */
-                            /*                 1 = MFMA 32x32x8 fp16 tiles                            */
+    int32_t slots;          /* sub-vectors per K tile: 32 or 64 (64 only for m <= 2)                  */
+    int32_t waves;          /* wavefronts per workgroup, 8 or 16; they split the slots of a tile,     */
+                            /* (slots / waves) * m must not exceed 8                                   */
+    int32_t k_splits;       /* workgroups per 512-row block, each taking a contiguous range of K      */
+                            /* tiles (clamped to the number of K tiles); their partial sums are       */
+                            /* combined through the workspace                                          */
+    int32_t batch_group;    /* batch rows handled per pass over the codes: 1, 2 or 4                  */
     int32_t reserved[4];    /* must be zero */
 } codegemm_plan;
 
@@ -109,6 +111,7 @@ int codegemm_workspace_init(void *workspace, size_t workspace_bytes, void *strea
  *
  * Packed layout.  Let S = plan.slots, J = K / v, NRB = ceil(N / 512),
  * NKT = ceil(J / S).  The buffer is an array [NRB][NKT][S][part][64][bytes]
+ * (all units of one 512-row block are contiguous, in K order),
  * where the step index t runs over 0..S-1, the lane index l over 0..63, and the
  * 8*m bytes a lane reads per step are split into parts of 16 bytes (two
  * codebooks) plus, for odd m, a last part of 8 bytes (one codebook).  Within a
@@ -140,9 +143,10 @@ int codegemm_psumbook_build(const codegemm_desc *desc, const void *x, const void
  * The hot path (Section 3, Steps 1-3, then de-normalisation by the row scale):
  *     y[b][n] = scales[n] * sum_{c<m} sum_{j<K/v} P[b][c][j][ codes[c][n][j] ].
  * `packed_codes` is the output of codegemm_pack_codes under the same plan.slots.
- * fp16 inputs, fp32 Psumbook and accumulation, y rounded to nearest-even fp16
- * (or stored as fp32 under CODEGEMM_FLAG_Y_FP32).  The partial sums of the
- * K tiles are combined in a fixed order, so results are bit-reproducible.
+ * fp16 inputs, fp32 Psumbook (built on the matrix cores: fp16 products are exact
+ * in fp32) and fp32 accumulation, y rounded to nearest-even fp16 (or stored as
+ * fp32 under CODEGEMM_FLAG_Y_FP32).  The partial sums of the K ranges are
+ * combined in a fixed order, so results are bit-reproducible.
  * `workspace` holds at least codegemm_workspace_bytes() bytes and has been
  * through codegemm_workspace_init once.  plan == NULL uses the default plan.
  */

@@ -44,15 +44,16 @@ class Desc(ctypes.Structure):
 
 class Plan(ctypes.Structure):
     """codegemm_plan"""
-    _fields_ = [("slots", ctypes.c_int32), ("row_waves", ctypes.c_int32), ("k_waves", ctypes.c_int32),
-                ("build", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4)]
+    _fields_ = [("slots", ctypes.c_int32), ("waves", ctypes.c_int32), ("k_splits", ctypes.c_int32),
+                ("batch_group", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4)]
 
     @classmethod
-    def make(cls, slots: int, row_waves: int, k_waves: int, build: int = 0):
-        return cls(slots, row_waves, k_waves, build, (ctypes.c_int32 * 4)(0, 0, 0, 0))
+    def make(cls, slots: int, waves: int, k_splits: int, batch_group: int = 1):
+        return cls(slots, waves, k_splits, batch_group, (ctypes.c_int32 * 4)(0, 0, 0, 0))
 
     def __repr__(self):
-        return f"Plan(slots={self.slots}, row_waves={self.row_waves}, k_waves={self.k_waves}, build={self.build})"
+        return (f"Plan(slots={self.slots}, waves={self.waves}, k_splits={self.k_splits}, "
+                f"batch_group={self.batch_group})")
 
 
 def lib_path() -> str:

@@ -24,14 +24,15 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 // Derived sizes of one problem under one plan.
 struct Geometry {
     int B, K, N, v, m, J;
-    int S;          // slots per K tile
-    int RW, JW;     // wavefronts per workgroup along N and along the tile's slots
-    int NSTEP;      // S / JW steps per wavefront
+    int S;          // slots (sub-vectors) per K tile
+    int NW;         // wavefronts per workgroup
+    int BG;         // batch rows per pass over the codes
     int NRB;        // ceil(N / 512) row blocks
     int NKT;        // ceil(J / S) K tiles
-    int NRT;        // ceil(NRB / RW) row tiles
+    int NKS;        // workgroups per row block (K ranges)
+    int KPW;        // K tiles per workgroup: ceil(NKT / NKS)
+    int NG;         // ceil(B / BG) batch groups
     int Npad;       // NRB * 512
-    int build;      // 0 VALU, 1 MFMA
     bool y_fp32;
 };
 
@@ -58,7 +59,6 @@ __host__ __device__ inline size_t packed_offset(int c, int n, int j, int m, int 
 
 int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g);   // status
 size_t workspace_counter_bytes(const Geometry& g);
-size_t lds_bytes_gemm(const Geometry& g);
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 

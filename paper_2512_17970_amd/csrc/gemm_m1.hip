@@ -1,0 +1,6 @@
+// Gather kernels for m = 1 codebooks (see gemm_impl.h).
+#include "gemm_impl.h"
+
+namespace cg {
+int launch_gemm_m1(const Geometry& g, const GemmParams& p, hipStream_t stream) { return launch_gemm_m<1>(g, p, stream); }
+}  // namespace cg

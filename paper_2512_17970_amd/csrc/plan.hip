@@ -16,44 +16,38 @@ static int validate_desc(const codegemm_desc* d)
     return CODEGEMM_OK;
 }
 
-static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
-
 static int validate_plan(const codegemm_desc* d, const codegemm_plan* p)
 {
+    const int m = d->num_codebooks;
     if (p->slots != 32 && p->slots != 64) return CODEGEMM_UNSUPPORTED;
-    if (!pow2(p->row_waves) || !pow2(p->k_waves)) return CODEGEMM_UNSUPPORTED;
-    if (p->row_waves * p->k_waves > 16) return CODEGEMM_UNSUPPORTED;
-    if (p->slots % p->k_waves) return CODEGEMM_UNSUPPORTED;
-    const int nstep = p->slots / p->k_waves;
-    if (nstep != 4 && nstep != 8 && nstep != 16) return CODEGEMM_UNSUPPORTED;
-    if (p->build != 0 && p->build != 1) return CODEGEMM_UNSUPPORTED;
+    if (p->waves != 8 && p->waves != 16) return CODEGEMM_UNSUPPORTED;
+    if (p->slots == 64 && m > 2) return CODEGEMM_UNSUPPORTED;                 // Psumbook would exceed LDS
+    if ((p->slots / p->waves) * m > 8) return CODEGEMM_UNSUPPORTED;           // code ring must fit in registers
+    if (p->k_splits < 1) return CODEGEMM_UNSUPPORTED;
+    if (p->batch_group != 1 && p->batch_group != 2 && p->batch_group != 4) return CODEGEMM_UNSUPPORTED;
     for (int i = 0; i < 4; ++i)
         if (p->reserved[i]) return CODEGEMM_INVALID_ARG;
-    const size_t planes = (size_t)d->num_codebooks * kCentroids * p->slots * sizeof(float);
-    const size_t staging = (size_t)d->num_codebooks * kCentroids * d->vec_len * 2 + (size_t)p->slots * d->vec_len * 2;
-    if (planes + staging + 64 > (size_t)kMaxLds) return CODEGEMM_UNSUPPORTED;
     return CODEGEMM_OK;
 }
 
-// Library's own choice of tile shape.  A tile is 512*row_waves rows by `slots`
-// sub-vectors.  The Psumbook is rebuilt once per tile, so tall tiles amortise the
-// build; but the grid must still cover the 256 compute units, so the tile height
-// is reduced until there are at least that many tiles.
+// Library's own choice.  One workgroup per compute unit is resident (its two Psumbook
+// buffers take 128 KB of LDS), so the K ranges are cut to give close to, but not more
+// than, 256 workgroups, each streaming a contiguous run of units.
 static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
 {
     *p = codegemm_plan{};
     const int m = d->num_codebooks;
     const int J = d->in_features / d->vec_len;
-    p->slots = (m <= 2) ? 64 : 32;
+    p->slots = (m == 1) ? 64 : 32;
+    p->waves = 16;
     const int nrb = ceil_div(d->out_features, kBlockRows);
     const int nkt = ceil_div(J, p->slots);
-    int rw = 4;
-    while (rw > 1 && (long)ceil_div(nrb, rw) * nkt < 224) rw >>= 1;
-    p->row_waves = rw;
-    int jw = 16 / rw;
-    if (p->slots / jw < 4) jw = p->slots / 4;
-    p->k_waves = jw;
-    p->build = 0;
+    int nks = 256 / nrb;
+    if (nks < 1) nks = 1;
+    if (nks > nkt) nks = nkt;
+    const int kpw = ceil_div(nkt, nks);
+    p->k_splits = ceil_div(nkt, kpw);             // no empty K range
+    p->batch_group = d->batch == 1 ? 1 : (d->batch == 2 ? 2 : 4);
 }
 
 int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g)
@@ -74,29 +68,22 @@ int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g
     g->m = d->num_codebooks;
     g->J = g->K / g->v;
     g->S = plan->slots;
-    g->RW = plan->row_waves;
-    g->JW = plan->k_waves;
-    g->NSTEP = g->S / g->JW;
+    g->NW = plan->waves;
+    g->BG = plan->batch_group;
     g->NRB = ceil_div(g->N, kBlockRows);
     g->NKT = ceil_div(g->J, g->S);
-    g->NRT = ceil_div(g->NRB, g->RW);
+    int nks = plan->k_splits < g->NKT ? plan->k_splits : g->NKT;
+    g->KPW = ceil_div(g->NKT, nks);
+    g->NKS = ceil_div(g->NKT, g->KPW);          // no empty K range
+    g->NG = ceil_div(g->B, g->BG);
     g->Npad = g->NRB * kBlockRows;
-    g->build = plan->build;
     g->y_fp32 = (d->flags & CODEGEMM_FLAG_Y_FP32) != 0;
     return CODEGEMM_OK;
 }
 
 size_t workspace_counter_bytes(const Geometry& g)
 {
-    return ((size_t)g.NRT * sizeof(uint32_t) + 255) & ~(size_t)255;
-}
-
-size_t lds_bytes_gemm(const Geometry& g)
-{
-    return (size_t)g.m * kCentroids * g.S * sizeof(float)      // Psumbook planes
-           + (size_t)g.m * kCentroids * g.v * 2                // codebook staging (fp16)
-           + (size_t)g.S * g.v * 2                             // x slice staging (fp16)
-           + 64;                                               // flags
+    return ((size_t)g.NG * g.NRB * sizeof(uint32_t) + 255) & ~(size_t)255;
 }
 
 }  // namespace cg
@@ -116,7 +103,7 @@ extern "C" size_t codegemm_workspace_bytes(const codegemm_desc* desc, const code
 {
     Geometry g;
     if (make_geometry(desc, plan, &g)) return 0;
-    return workspace_counter_bytes(g) + (size_t)g.B * g.NKT * g.Npad * sizeof(float);
+    return workspace_counter_bytes(g) + (size_t)g.B * g.NKS * g.Npad * sizeof(float);
 }
 
 extern "C" size_t codegemm_packed_codes_bytes(const codegemm_desc* desc, const codegemm_plan* plan)

@@ -39,12 +39,13 @@ def test_default_plans_are_valid_for_all_workloads():
         for c in cases:
             d = cg.Desc.make(c.B, c.K, c.N, c.v, c.m)
             p = cg.codegemm_default_plan(d)
-            assert p.slots in (32, 64) and p.row_waves * p.k_waves <= 16
-            assert c.m * 256 * p.slots * 4 <= 160 * 1024
+            assert p.slots in (32, 64) and p.waves in (8, 16) and p.batch_group in (1, 2, 4)
+            assert (p.slots // p.waves) * c.m <= 8
             nrb = -(-c.N // 512)
             nkt = -(-c.J // p.slots)
+            assert 1 <= p.k_splits <= nkt and nrb * p.k_splits <= max(256, nrb)
             assert cg.codegemm_packed_codes_bytes(d) == nrb * nkt * p.slots * 64 * 8 * c.m
-            assert cg.codegemm_workspace_bytes(d) >= c.B * nkt * nrb * 512 * 4
+            assert cg.codegemm_workspace_bytes(d) >= c.B * p.k_splits * nrb * 512 * 4 * (nkt > 1)
 
 
 def test_invalid_descriptors_are_rejected():
@@ -59,12 +60,14 @@ def test_invalid_descriptors_are_rejected():
 
 def test_invalid_plans_are_rejected():
     d = cg.Desc.make(1, 512, 512, 8, 2)
-    for p in (cg.Plan.make(48, 1, 4), cg.Plan.make(64, 3, 4), cg.Plan.make(64, 4, 8), cg.Plan.make(64, 1, 2),
-              cg.Plan.make(64, 1, 4, build=7)):
+    for p in (cg.Plan.make(48, 16, 4), cg.Plan.make(64, 4, 4), cg.Plan.make(64, 8, 4), cg.Plan.make(32, 16, 0),
+              cg.Plan.make(32, 16, 2, 3), cg.Plan.make(32, 32, 1)):
         assert cg.codegemm_workspace_bytes(d, p) == 0
+    assert cg.codegemm_workspace_bytes(d, cg.Plan.make(64, 16, 4)) > 0
     d3 = cg.Desc.make(1, 512, 512, 8, 3)
-    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(64, 1, 4)) == 0      # 192 KB of planes does not fit
-    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(32, 1, 4)) > 0
+    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(64, 16, 2)) == 0      # 192 KB of Psumbook does not fit
+    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(32, 8, 2)) == 0       # 4 steps x 3 codebooks of code words
+    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(32, 16, 2)) > 0
 
 
 def test_compressed_bytes_closed_form():

@@ -54,15 +54,35 @@ def test_tiny_config(y_fp32):
     run_case(synth.workloads()[1][0], y_fp32=y_fp32)
 
 
-PLANS = [(64, 1, 16), (64, 1, 8), (64, 1, 4), (64, 2, 8), (64, 2, 4), (64, 4, 4),
-         (32, 1, 8), (32, 1, 4), (32, 1, 2), (32, 2, 8), (32, 4, 4), (32, 8, 2), (32, 2, 2)]
+def valid_plans(m):
+    out = [(32, 16)]
+    if m <= 2:
+        out += [(64, 16), (32, 8)]
+    if m == 1:
+        out += [(64, 8)]
+    return out
 
 
-@pytest.mark.parametrize("slots,rw,jw", PLANS)
-@pytest.mark.parametrize("v,m", [(8, 2), (4, 1)])
-def test_every_plan_shape(slots, rw, jw, v, m):
-    case = synth.custom_case(v * 200, 1300, v, m, 1, seed=99)
-    run_case(case, plan=cg.Plan.make(slots, rw, jw), dequant=False)
+@pytest.mark.parametrize("k_splits", [1, 3, 1000])
+@pytest.mark.parametrize("v,m", [(8, 2), (4, 1), (8, 1), (4, 2), (8, 3), (4, 4), (8, 4), (4, 3)])
+def test_every_plan_shape(v, m, k_splits):
+    for slots, waves in valid_plans(m):
+        case = synth.custom_case(v * 200, 1300, v, m, 1, seed=99)
+        run_case(case, plan=cg.Plan.make(slots, waves, k_splits, 1), dequant=False)
+
+
+@pytest.mark.parametrize("B,bg", [(2, 1), (2, 2), (3, 2), (3, 4), (4, 4), (5, 4), (8, 4), (8, 1), (32, 4), (7, 2)])
+@pytest.mark.parametrize("v,m,slots", [(8, 2, 32), (8, 2, 64), (4, 1, 64), (8, 3, 32)])
+def test_batch_groups(B, bg, v, m, slots):
+    case = synth.custom_case(v * 150, 1100, v, m, B, seed=98)
+    run_case(case, plan=cg.Plan.make(slots, 16, 2, bg), dequant=False)
+
+
+def test_many_units_per_workgroup():
+    """A long K range per workgroup: the code ring wraps many times, with a ragged last tile."""
+    for (v, m, slots, splits) in [(8, 2, 32, 1), (8, 2, 32, 2), (4, 1, 64, 1), (8, 4, 32, 3), (8, 2, 64, 1)]:
+        case = synth.custom_case(v * (32 * 37 + 5), 600, v, m, 1, seed=97)
+        run_case(case, plan=cg.Plan.make(slots, 16, splits, 1), dequant=False)
 
 
 def test_pack_matches_documented_layout_and_roundtrips():
@@ -72,7 +92,7 @@ def test_pack_matches_documented_layout_and_roundtrips():
         desc = cg.Desc.make(1, K, N, v, m)
         for slots in ([32, 64] if m <= 2 else [32]):
             say(f"[pack] {case.name} slots={slots}")
-            plan = cg.Plan.make(slots, 1, slots // 4 if slots // 4 <= 16 else 16)
+            plan = cg.Plan.make(slots, 16, 2)
             nbytes = cg.codegemm_packed_codes_bytes(desc, plan)
             want = pack_reference(inp.codes, slots)
             assert nbytes == want.size
@@ -154,6 +174,6 @@ def test_error_paths():
     with pytest.raises(cg.CodegemmError):
         cg.codegemm_gemm(d, None, None, t, t, t, t, t, 1 << 20)                                  # NULL
     with pytest.raises(cg.CodegemmError):
-        cg.codegemm_gemm(d, cg.Plan.make(48, 1, 4), t, t, t, t, t, t, 1 << 20)                   # plan
+        cg.codegemm_gemm(d, cg.Plan.make(48, 16, 4), t, t, t, t, t, t, 1 << 20)                   # plan
     with pytest.raises(cg.CodegemmError):
         cg.codegemm_gemm(d, None, t[1:], t, t, t, t, t, 1 << 20)                                 # alignment
