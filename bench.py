@@ -44,7 +44,7 @@ def parse():
                     help="graph: the K timed steps are one captured HIP graph (no host launch cost); direct: plain launches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true", help="skip the per-shape cold/warm/dequant table")
-    ap.add_argument("--plan", default="", help="override plan for every shape: slots,waves,k_splits[,batch_group]")
+    ap.add_argument("--plan", default="", help="override plan for every shape: waves,row_words,k_splits[,batch_group]")
     return ap.parse_args()
 
 

@@ -68,20 +68,20 @@ typedef struct codegemm_desc {
 
 /*
  * Launch plan of codegemm_gemm (host struct).  The paper's tile is t_h rows by
- * t_w weights (Section 3); here one "unit" is 512 rows by slots * v weights, and
- * one workgroup streams through a contiguous run of units of one 512-row block
- * (all of K when k_splits = 1), rebuilding the Psumbook (m * 256 * slots fp32
- * in LDS, double-buffered when two copies fit in 128 KB) once per unit.
- * `slots` also fixes the packed code layout: codes packed under one value of
- * `slots` can only be used with plans of the same `slots`.
+ * t_w weights (Section 3); here one "unit" is 128 rows by 32 * v weights, and one
+ * workgroup streams through a contiguous run of units of its rows (all of K when
+ * k_splits = 1), rebuilding the Psumbook (m * 256 * 32 fp32 in LDS, double-
+ * buffered for m <= 2) once per unit.
  */
 typedef struct codegemm_plan {
-    int32_t slots;          /* sub-vectors per K tile: 32 or 64 (64 only for m <= 2)                  */
-    int32_t waves;          /* wavefronts per workgroup, 8 or 16; they split the slots of a tile,     */
-                            /* (slots / waves) * m must not exceed 8                                   */
-    int32_t k_splits;       /* workgroups per 512-row block, each taking a contiguous range of K      */
-                            /* tiles (clamped to the number of K tiles); their partial sums are       */
-                            /* combined through the workspace                                          */
+    int32_t waves;          /* wavefronts per workgroup: 8 or 16                                      */
+    int32_t row_words;      /* 8-row code words per lane per unit: 1, 2 or 4 (4 needs waves = 16,     */
+                            /* batch_group = 1, m <= 2; 2 needs batch_group * m <= 4).  The workgroup */
+                            /* owns 16 * waves * row_words rows                                       */
+    int32_t k_splits;       /* workgroups per row block, each taking a contiguous range of K tiles    */
+                            /* (clamped to the number of K tiles).  1: every workgroup produces final */
+                            /* outputs on its own.  > 1: partial sums are combined through the        */
+                            /* workspace by the last workgroup to finish                               */
     int32_t batch_group;    /* batch rows handled per pass over the codes: 1, 2 or 4                  */
     int32_t reserved[4];    /* must be zero */
 } codegemm_plan;
@@ -109,19 +109,21 @@ int codegemm_workspace_init(void *workspace, size_t workspace_bytes, void *strea
  * Re-orders canonical codes [m][N][K/v] into the packed streaming layout the
  * gather kernel reads (offline, once per weight matrix), and back.
  *
- * Packed layout.  Let S = plan.slots, J = K / v, NRB = ceil(N / 512),
- * NKT = ceil(J / S).  The buffer is an array [NRB][NKT][S][part][64][bytes]
- * (all units of one 512-row block are contiguous, in K order),
- * where the step index t runs over 0..S-1, the lane index l over 0..63, and the
- * 8*m bytes a lane reads per step are split into parts of 16 bytes (two
- * codebooks) plus, for odd m, a last part of 8 bytes (one codebook).  Within a
- * part, byte 8*(c - c0) + r holds, for codebook c and r = 0..7,
- *     codes[c][512*rb + 64*r + l][S*kt + ((t + l) mod S)]
- * or 0 when that row or sub-vector lies outside the matrix.  The rotation by
- * the lane index makes the 64 lanes of a wavefront read 64 different slots of
- * the Psumbook in every step, which keeps the data-dependent LDS gathers free
- * of bank conflicts whatever the code values are.  Bytes are stored as such,
- * so a 32-bit word read from the buffer holds byte q in bits 8q..8q+7.
+ * Packed layout (independent of the plan).  Let J = K / v, NGR = ceil(N / 128),
+ * NKT = ceil(J / 32).  The buffer is an array [NGR][NKT][part][16][32][bytes]:
+ * one "unit" per 128-row granule rg and K tile kt (all units of a granule are
+ * contiguous, in K order); inside a unit the index g = 0..15 selects 8 rows,
+ * s = 0..31 a sub-vector of the tile, and the 8*m bytes of (g, s) are split
+ * into parts of 16 bytes (two codebooks) plus, for odd m, a last part of 8
+ * bytes (one codebook).  Within a part, byte 8*(c - c0) + r holds, for
+ * codebook c and r = 0..7,
+ *     codes[c][128*rg + 8*g + r][32*kt + s]
+ * or 0 when that row or sub-vector lies outside the matrix.  A wavefront reads
+ * 64 consecutive entries (two values of g, all 32 slots) with one 16-byte load
+ * per lane, and the 32 lanes of each half-wavefront then address 32 different
+ * slots of the Psumbook, which keeps the data-dependent LDS gathers free of
+ * bank conflicts whatever the code values are.  Bytes are stored as such, so a
+ * 32-bit word read from the buffer holds byte q in bits 8q..8q+7.
  *
  * Both calls are bit-exact: unpack(pack(codes)) == codes.
  */
@@ -142,11 +144,11 @@ int codegemm_psumbook_build(const codegemm_desc *desc, const void *x, const void
 /*
  * The hot path (Section 3, Steps 1-3, then de-normalisation by the row scale):
  *     y[b][n] = scales[n] * sum_{c<m} sum_{j<K/v} P[b][c][j][ codes[c][n][j] ].
- * `packed_codes` is the output of codegemm_pack_codes under the same plan.slots.
+ * `packed_codes` is the output of codegemm_pack_codes.
  * fp16 inputs, fp32 Psumbook (built on the matrix cores: fp16 products are exact
  * in fp32) and fp32 accumulation, y rounded to nearest-even fp16 (or stored as
- * fp32 under CODEGEMM_FLAG_Y_FP32).  The partial sums of the K ranges are
- * combined in a fixed order, so results are bit-reproducible.
+ * fp32 under CODEGEMM_FLAG_Y_FP32).  Every sum is taken in a fixed order (also
+ * across K ranges), so results are bit-reproducible.
  * `workspace` holds at least codegemm_workspace_bytes() bytes and has been
  * through codegemm_workspace_init once.  plan == NULL uses the default plan.
  */

@@ -44,15 +44,15 @@ class Desc(ctypes.Structure):
 
 class Plan(ctypes.Structure):
     """codegemm_plan"""
-    _fields_ = [("slots", ctypes.c_int32), ("waves", ctypes.c_int32), ("k_splits", ctypes.c_int32),
+    _fields_ = [("waves", ctypes.c_int32), ("row_words", ctypes.c_int32), ("k_splits", ctypes.c_int32),
                 ("batch_group", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4)]
 
     @classmethod
-    def make(cls, slots: int, waves: int, k_splits: int, batch_group: int = 1):
-        return cls(slots, waves, k_splits, batch_group, (ctypes.c_int32 * 4)(0, 0, 0, 0))
+    def make(cls, waves: int, row_words: int, k_splits: int, batch_group: int = 1):
+        return cls(waves, row_words, k_splits, batch_group, (ctypes.c_int32 * 4)(0, 0, 0, 0))
 
     def __repr__(self):
-        return (f"Plan(slots={self.slots}, waves={self.waves}, k_splits={self.k_splits}, "
+        return (f"Plan(waves={self.waves}, row_words={self.row_words}, k_splits={self.k_splits}, "
                 f"batch_group={self.batch_group})")
 
 

@@ -11,7 +11,8 @@ namespace cg {
 constexpr int kCentroids = 256;     // 2^b with b = 8
 constexpr int kWave = 64;           // CDNA wavefront width
 constexpr int kRowsPerLane = 8;     // output rows owned by one lane of the gather kernel
-constexpr int kBlockRows = kWave * kRowsPerLane;   // 512 rows per wavefront
+constexpr int kSlots = 32;          // sub-vectors per K tile = lanes of a half-wavefront
+constexpr int kGranuleRows = 128;   // rows per packed unit: 16 half-wavefronts x 8 rows
 constexpr int kMaxLds = 160 * 1024; // LDS per workgroup on gfx950
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
@@ -24,36 +25,33 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 // Derived sizes of one problem under one plan.
 struct Geometry {
     int B, K, N, v, m, J;
-    int S;          // slots (sub-vectors) per K tile
-    int NW;         // wavefronts per workgroup
+    int NW;         // wavefronts per workgroup (8 or 16)
+    int RPL;        // 8-row words per lane per unit (1, 2 or 4): the workgroup owns 16 * NW * RPL rows
     int BG;         // batch rows per pass over the codes
-    int NRB;        // ceil(N / 512) row blocks
-    int NKT;        // ceil(J / S) K tiles
+    int NGR;        // ceil(N / 128) granules
+    int NBLK;       // row blocks = workgroups along N: ceil(NGR / (RPL * NW / 8))
+    int NKT;        // ceil(J / 32) K tiles
     int NKS;        // workgroups per row block (K ranges)
     int KPW;        // K tiles per workgroup: ceil(NKT / NKS)
     int NG;         // ceil(B / BG) batch groups
-    int Npad;       // NRB * 512
+    int Npad;       // NGR * 128
     bool y_fp32;
 };
 
 __host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// Bytes one lane reads per step, and per-step bytes of a whole wavefront.
-__host__ __device__ inline int step_bytes(int m) { return kWave * kRowsPerLane * m; }
-
 // Offset of the packed byte that holds codes[c][n][j]  (see codegemm.h, packed layout).
-__host__ __device__ inline size_t packed_offset(int c, int n, int j, int m, int S, int NKT)
+__host__ __device__ inline size_t packed_offset(int c, int n, int j, int m, int NKT)
 {
-    const int rb = n / kBlockRows;
-    const int r = (n % kBlockRows) / kWave;
-    const int l = n % kWave;
-    const int kt = j / S;
-    const int slot = j % S;
-    const int t = (slot - l) & (S - 1);
+    const int granule = n / kGranuleRows;
+    const int g = (n % kGranuleRows) / kRowsPerLane;       // row-lane: which half-wavefront
+    const int r = n % kRowsPerLane;
+    const int kt = j / kSlots;
+    const int s = j % kSlots;
     const int part = c >> 1;
     const int part_bytes = (2 * part + 1 == m) ? 8 : 16;   // last part of an odd m holds one codebook
-    size_t off = (((size_t)rb * NKT + kt) * S + t) * (size_t)step_bytes(m);
-    off += (size_t)part * 16 * kWave + (size_t)l * part_bytes + (c & 1) * 8 + r;
+    size_t off = ((size_t)granule * NKT + kt) * (size_t)(kGranuleRows * kSlots * m);
+    off += (size_t)part * 16 * 512 + (size_t)(g * kSlots + s) * part_bytes + (c & 1) * 8 + r;
     return off;
 }
 

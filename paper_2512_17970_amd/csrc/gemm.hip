@@ -58,7 +58,7 @@ extern "C" int codegemm_gemm(const codegemm_desc* desc, const codegemm_plan* pla
     p.counters = static_cast<uint32_t*>(workspace);
     p.partials = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + cbytes);
     p.B = g.B; p.K = g.K; p.N = g.N;
-    p.NRB = g.NRB; p.NKT = g.NKT; p.NKS = g.NKS; p.KPW = g.KPW; p.Npad = g.Npad;
+    p.NGR = g.NGR; p.NKT = g.NKT; p.NKS = g.NKS; p.KPW = g.KPW; p.Npad = g.Npad;
     p.y_fp32 = g.y_fp32 ? 1 : 0;
     p.trace = nullptr;
 #ifdef CODEGEMM_TRACE

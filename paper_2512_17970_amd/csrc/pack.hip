@@ -8,7 +8,7 @@ namespace cg {
 // written exactly once, positions outside the matrix get code 0.
 __global__ void __launch_bounds__(256)
 pack_kernel(const uint8_t* __restrict__ codes, uint8_t* __restrict__ packed,
-            int N, int J, int m, int S, int NKT, int Npad, int Jpad)
+            int N, int J, int m, int NKT, int Npad, int Jpad)
 {
     const size_t total = (size_t)m * Npad * Jpad;
     for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
@@ -18,13 +18,13 @@ pack_kernel(const uint8_t* __restrict__ codes, uint8_t* __restrict__ packed,
         const int c = (int)(idx / ((size_t)Jpad * Npad));
         uint8_t code = 0;
         if (n < N && j < J) code = codes[((size_t)c * N + n) * J + j];
-        packed[packed_offset(c, n, j, m, S, NKT)] = code;
+        packed[packed_offset(c, n, j, m, NKT)] = code;
     }
 }
 
 __global__ void __launch_bounds__(256)
 unpack_kernel(const uint8_t* __restrict__ packed, uint8_t* __restrict__ codes,
-              int N, int J, int m, int S, int NKT)
+              int N, int J, int m, int NKT)
 {
     const size_t total = (size_t)m * N * J;
     for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
@@ -32,7 +32,7 @@ unpack_kernel(const uint8_t* __restrict__ packed, uint8_t* __restrict__ codes,
         const int j = (int)(idx % J);
         const int n = (int)((idx / J) % N);
         const int c = (int)(idx / ((size_t)J * N));
-        codes[idx] = packed[packed_offset(c, n, j, m, S, NKT)];
+        codes[idx] = packed[packed_offset(c, n, j, m, NKT)];
     }
 }
 
@@ -62,10 +62,10 @@ extern "C" int codegemm_pack_codes(const codegemm_desc* desc, const codegemm_pla
     int st = make_geometry(desc, plan, &g);
     if (st) return st;
     if (!codes || !packed || misaligned(codes) || misaligned(packed)) return CODEGEMM_INVALID_ARG;
-    const int Jpad = g.NKT * g.S;
+    const int Jpad = g.NKT * kSlots;
     const size_t total = (size_t)g.m * g.Npad * Jpad;
     hipLaunchKernelGGL(pack_kernel, dim3(grid_for(total)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       codes, packed, g.N, g.J, g.m, g.S, g.NKT, g.Npad, Jpad);
+                       codes, packed, g.N, g.J, g.m, g.NKT, g.Npad, Jpad);
     return hipGetLastError() == hipSuccess ? CODEGEMM_OK : CODEGEMM_LAUNCH_FAILED;
 }
 
@@ -78,7 +78,7 @@ extern "C" int codegemm_unpack_codes(const codegemm_desc* desc, const codegemm_p
     if (!codes || !packed || misaligned(codes) || misaligned(packed)) return CODEGEMM_INVALID_ARG;
     const size_t total = (size_t)g.m * g.N * g.J;
     hipLaunchKernelGGL(unpack_kernel, dim3(grid_for(total)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       packed, codes, g.N, g.J, g.m, g.S, g.NKT);
+                       packed, codes, g.N, g.J, g.m, g.NKT);
     return hipGetLastError() == hipSuccess ? CODEGEMM_OK : CODEGEMM_LAUNCH_FAILED;
 }
 

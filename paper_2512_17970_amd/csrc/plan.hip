@@ -18,36 +18,42 @@ static int validate_desc(const codegemm_desc* d)
 
 static int validate_plan(const codegemm_desc* d, const codegemm_plan* p)
 {
-    const int m = d->num_codebooks;
-    if (p->slots != 32 && p->slots != 64) return CODEGEMM_UNSUPPORTED;
     if (p->waves != 8 && p->waves != 16) return CODEGEMM_UNSUPPORTED;
-    if (p->slots == 64 && m > 2) return CODEGEMM_UNSUPPORTED;                 // Psumbook would exceed LDS
-    if ((p->slots / p->waves) * m > 8) return CODEGEMM_UNSUPPORTED;           // code ring must fit in registers
+    if (p->row_words != 1 && p->row_words != 2 && p->row_words != 4) return CODEGEMM_UNSUPPORTED;
+    if (p->row_words == 4 && p->waves != 16) return CODEGEMM_UNSUPPORTED;
     if (p->k_splits < 1) return CODEGEMM_UNSUPPORTED;
     if (p->batch_group != 1 && p->batch_group != 2 && p->batch_group != 4) return CODEGEMM_UNSUPPORTED;
     for (int i = 0; i < 4; ++i)
         if (p->reserved[i]) return CODEGEMM_INVALID_ARG;
+    const int m = d->num_codebooks;
+    if (p->row_words >= 2 && p->batch_group * m > 4) return CODEGEMM_UNSUPPORTED;   // accumulators + code ring must fit in registers
+    if (p->row_words == 4 && (p->batch_group != 1 || m > 2)) return CODEGEMM_UNSUPPORTED;
     return CODEGEMM_OK;
 }
 
-// Library's own choice.  One workgroup per compute unit is resident (its two Psumbook
-// buffers take 128 KB of LDS), so the K ranges are cut to give close to, but not more
-// than, 256 workgroups, each streaming a contiguous run of units.
+// Library's own choice.  One workgroup per compute unit is resident (its Psumbook
+// buffers take 128 KB of LDS).  A workgroup must stream about 32 KB of codes per K tile
+// to keep up with its share of HBM, so blocks are 512 rows tall when the batch and the
+// number of codebooks leave registers for it; the K ranges are then cut to give close
+// to, but not more than, 256 workgroups.
 static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
 {
     *p = codegemm_plan{};
     const int m = d->num_codebooks;
     const int J = d->in_features / d->vec_len;
-    p->slots = (m == 1) ? 64 : 32;
-    p->waves = 16;
-    const int nrb = ceil_div(d->out_features, kBlockRows);
-    const int nkt = ceil_div(J, p->slots);
-    int nks = 256 / nrb;
-    if (nks < 1) nks = 1;
-    if (nks > nkt) nks = nkt;
-    const int kpw = ceil_div(nkt, nks);
-    p->k_splits = ceil_div(nkt, kpw);             // no empty K range
+    const int ngr = ceil_div(d->out_features, kGranuleRows);
+    const int nkt = ceil_div(J, kSlots);
     p->batch_group = d->batch == 1 ? 1 : (d->batch == 2 ? 2 : 4);
+    // 512-row blocks for large matrices, 256-row blocks (more, shorter K ranges) below ~32 MB of codes
+    const double code_bytes = (double)m * d->out_features * J;
+    p->waves = (code_bytes >= 32e6) ? 16 : 8;
+    p->row_words = (p->batch_group * m <= 4) ? 2 : 1;
+    const int nblk = ceil_div(ngr, p->row_words * p->waves / 8);
+    int nks = 256 / nblk;
+    if (nks > nkt) nks = nkt;
+    if (nks < 1) nks = 1;
+    const int kpw = ceil_div(nkt, nks);
+    p->k_splits = ceil_div(nkt, kpw);                     // no empty K range
 }
 
 int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g)
@@ -67,23 +73,24 @@ int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g
     g->v = d->vec_len;
     g->m = d->num_codebooks;
     g->J = g->K / g->v;
-    g->S = plan->slots;
     g->NW = plan->waves;
+    g->RPL = plan->row_words;
     g->BG = plan->batch_group;
-    g->NRB = ceil_div(g->N, kBlockRows);
-    g->NKT = ceil_div(g->J, g->S);
+    g->NGR = ceil_div(g->N, kGranuleRows);
+    g->NBLK = ceil_div(g->NGR, g->RPL * g->NW / 8);
+    g->NKT = ceil_div(g->J, kSlots);
     int nks = plan->k_splits < g->NKT ? plan->k_splits : g->NKT;
     g->KPW = ceil_div(g->NKT, nks);
     g->NKS = ceil_div(g->NKT, g->KPW);          // no empty K range
     g->NG = ceil_div(g->B, g->BG);
-    g->Npad = g->NRB * kBlockRows;
+    g->Npad = g->NGR * kGranuleRows;
     g->y_fp32 = (d->flags & CODEGEMM_FLAG_Y_FP32) != 0;
     return CODEGEMM_OK;
 }
 
 size_t workspace_counter_bytes(const Geometry& g)
 {
-    return ((size_t)g.NG * g.NRB * sizeof(uint32_t) + 255) & ~(size_t)255;
+    return ((size_t)g.NG * g.NBLK * sizeof(uint32_t) + 255) & ~(size_t)255;
 }
 
 }  // namespace cg
@@ -110,7 +117,7 @@ extern "C" size_t codegemm_packed_codes_bytes(const codegemm_desc* desc, const c
 {
     Geometry g;
     if (make_geometry(desc, plan, &g)) return 0;
-    return (size_t)g.NRB * g.NKT * g.S * step_bytes(g.m);
+    return (size_t)g.NGR * g.NKT * kGranuleRows * kSlots * g.m;
 }
 
 extern "C" const char* codegemm_status_string(int status)

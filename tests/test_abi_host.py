@@ -39,13 +39,14 @@ def test_default_plans_are_valid_for_all_workloads():
         for c in cases:
             d = cg.Desc.make(c.B, c.K, c.N, c.v, c.m)
             p = cg.codegemm_default_plan(d)
-            assert p.slots in (32, 64) and p.waves in (8, 16) and p.batch_group in (1, 2, 4)
-            assert (p.slots // p.waves) * c.m <= 8
-            nrb = -(-c.N // 512)
-            nkt = -(-c.J // p.slots)
-            assert 1 <= p.k_splits <= nkt and nrb * p.k_splits <= max(256, nrb)
-            assert cg.codegemm_packed_codes_bytes(d) == nrb * nkt * p.slots * 64 * 8 * c.m
-            assert cg.codegemm_workspace_bytes(d) >= c.B * p.k_splits * nrb * 512 * 4 * (nkt > 1)
+            assert p.waves in (8, 16) and p.batch_group in (1, 2, 4)
+            ngr = -(-c.N // 128)
+            nkt = -(-c.J // 32)
+            assert p.row_words in (1, 2, 4)
+            nblk = -(-ngr // (p.row_words * p.waves // 8))
+            assert 1 <= p.k_splits <= nkt and nblk * p.k_splits <= max(256, nblk)
+            assert cg.codegemm_packed_codes_bytes(d) == ngr * 128 * nkt * 32 * c.m
+            assert cg.codegemm_workspace_bytes(d) >= c.B * p.k_splits * ngr * 128 * 4
 
 
 def test_invalid_descriptors_are_rejected():
@@ -60,14 +61,14 @@ def test_invalid_descriptors_are_rejected():
 
 def test_invalid_plans_are_rejected():
     d = cg.Desc.make(1, 512, 512, 8, 2)
-    for p in (cg.Plan.make(48, 16, 4), cg.Plan.make(64, 4, 4), cg.Plan.make(64, 8, 4), cg.Plan.make(32, 16, 0),
-              cg.Plan.make(32, 16, 2, 3), cg.Plan.make(32, 32, 1)):
+    for p in (cg.Plan.make(4, 1, 4), cg.Plan.make(12, 1, 4), cg.Plan.make(32, 1, 1), cg.Plan.make(16, 1, 0),
+              cg.Plan.make(16, 1, 2, 3), cg.Plan.make(16, 3, 1), cg.Plan.make(8, 4, 1), cg.Plan.make(16, 4, 1, 2)):
         assert cg.codegemm_workspace_bytes(d, p) == 0
-    assert cg.codegemm_workspace_bytes(d, cg.Plan.make(64, 16, 4)) > 0
-    d3 = cg.Desc.make(1, 512, 512, 8, 3)
-    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(64, 16, 2)) == 0      # 192 KB of Psumbook does not fit
-    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(32, 8, 2)) == 0       # 4 steps x 3 codebooks of code words
-    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(32, 16, 2)) > 0
+    for p in (cg.Plan.make(8, 1, 1), cg.Plan.make(16, 2, 4, 2), cg.Plan.make(8, 1, 100000, 4), cg.Plan.make(16, 4, 2)):
+        assert cg.codegemm_workspace_bytes(d, p) > 0
+    d3 = cg.Desc.make(4, 512, 512, 8, 3)
+    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(16, 2, 1, 4)) == 0    # 4 rows x 3 codebooks x 16 rows per lane
+    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(16, 1, 1, 4)) > 0
 
 
 def test_compressed_bytes_closed_form():
