@@ -39,11 +39,13 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c3", help="c2 | c3 | c5 | a single case name from synth.workloads()")
+    ap.add_argument("--workload", default="c3", help="c1..c5 | a single case name from synth.workloads()")
     ap.add_argument("--launch", default="graph", choices=["graph", "direct"],
                     help="graph: the K timed steps are one captured HIP graph (no host launch cost); direct: plain launches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true", help="skip the per-shape cold/warm/dequant table")
+    ap.add_argument("--psumbook", action="store_true",
+                    help="instead of the GEMM: time the stand-alone Psumbook build (vector ALU and MFMA) at batch 1, 8, 32")
     ap.add_argument("--plan", default="", help="override plan for every shape: waves,row_words,k_splits[,batch_group]")
     return ap.parse_args()
 
@@ -166,6 +168,26 @@ def cpu_baseline(cases, synth, budget_s=12.0):
             "ms_per_step": total_s * 1e3, "detail": detail}
 
 
+def psumbook_bench(torch, cg, synth):
+    """Stand-alone Eq. 2 build for the batch-sweep shapes: us per call, vector ALU vs matrix cores."""
+    for K in (4096, 14336):
+        for B in (1, 8, 32):
+            case = synth.custom_case(K, 256, 8, 2, B, seed=3)
+            inp = synth.generate(case)
+            desc = cg.Desc.make(B, K, 256, 8, 2)
+            x = torch.from_numpy(inp.x).cuda()
+            cb = torch.from_numpy(inp.codebooks).cuda()
+            P = torch.empty((B, 2, K // 8, 256), dtype=torch.float32, device="cuda")
+            for use_mfma in (False, True):
+                fn = lambda: cg.codegemm_psumbook_build(desc, x, cb, P, use_mfma, torch.cuda.current_stream().cuda_stream)
+                for _ in range(5):
+                    fn()
+                us = min(time_region(torch, fn, 50) * 1e3 / 50 for _ in range(3))
+                macs = 2 * 256 * K * B
+                log(f"  psumbook_build K={K} B={B} {'mfma' if use_mfma else 'valu'}: {us:.2f} us, "
+                    f"{P.numel() * 4 / us * 1e-3:.0f} GB/s written, {2 * macs / us * 1e-6:.2f} TFLOP/s")
+
+
 def read_traffic():
     """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
     path = os.path.join(ROOT, "profiles", "gemm_kernel_c3_pmc.txt")
@@ -191,9 +213,12 @@ def main():
         print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     cg.load()
+    if args.psumbook:
+        psumbook_bench(torch, cg, synth)
+        return
     wl = synth.workloads()
     key = args.workload.lower()
-    if key in ("c2", "c3", "c5"):
+    if key in ("c1", "c2", "c3", "c4", "c5"):
         cases = wl[int(key[1])]
     else:
         cases = [synth.find_case(args.workload)]
