@@ -76,7 +76,8 @@ typedef struct codegemm_desc {
 typedef struct codegemm_plan {
     int32_t waves;          /* wavefronts per workgroup: 8 or 16                                      */
     int32_t row_words;      /* 8-row code words per lane per unit: 1, 2 or 4 (4 needs waves = 16,     */
-                            /* batch_group = 1, m <= 2; 2 needs batch_group * m <= 4).  The workgroup */
+                            /* batch_group = 1, m <= 2; 2 needs batch_group * m <= 4, or <= 8 with    */
+                            /* waves = 8).  The workgroup                                             */
                             /* owns 16 * waves * row_words rows                                       */
     int32_t k_splits;       /* workgroups per row block, each taking a contiguous range of K tiles    */
                             /* (clamped to the number of K tiles).  1: every workgroup produces final */

@@ -456,6 +456,8 @@ int launch_gemm_mvb(const Geometry& g, const GemmParams& p, hipStream_t stream)
     if (g.NW == 16 && g.RPL == 1) return launch_gemm_one<M, V, 16, 1, BG, 8>(g, p, stream);
     if constexpr (BG * M <= 4) {
         if (g.NW == 16 && g.RPL == 2) return launch_gemm_one<M, V, 16, 2, BG, 4>(g, p, stream);
+    }
+    if constexpr (BG * M <= 8) {   // 8 wavefronts have twice the registers per lane
         if (g.NW == 8 && g.RPL == 2) return launch_gemm_one<M, V, 8, 2, BG, 4>(g, p, stream);
     }
     if constexpr (BG == 1 && M <= 2) {

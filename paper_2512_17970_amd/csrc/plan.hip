@@ -26,7 +26,7 @@ static int validate_plan(const codegemm_desc* d, const codegemm_plan* p)
     for (int i = 0; i < 4; ++i)
         if (p->reserved[i]) return CODEGEMM_INVALID_ARG;
     const int m = d->num_codebooks;
-    if (p->row_words >= 2 && p->batch_group * m > 4) return CODEGEMM_UNSUPPORTED;   // accumulators + code ring must fit in registers
+    if (p->row_words >= 2 && p->batch_group * m > (p->waves == 8 ? 8 : 4)) return CODEGEMM_UNSUPPORTED;   // accumulators + code ring must fit in registers
     if (p->row_words == 4 && (p->batch_group != 1 || m > 2)) return CODEGEMM_UNSUPPORTED;
     return CODEGEMM_OK;
 }
@@ -46,8 +46,8 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
     p->batch_group = d->batch == 1 ? 1 : (d->batch == 2 ? 2 : 4);
     // 512-row blocks for large matrices, 256-row blocks (more, shorter K ranges) below ~32 MB of codes
     const double code_bytes = (double)m * d->out_features * J;
-    p->waves = (code_bytes >= 32e6) ? 16 : 8;
-    p->row_words = (p->batch_group * m <= 4) ? 2 : 1;
+    p->waves = (code_bytes >= 32e6 && p->batch_group * m <= 4) ? 16 : 8;
+    p->row_words = (p->batch_group * m <= (p->waves == 8 ? 8 : 4)) ? 2 : 1;
     const int nblk = ceil_div(ngr, p->row_words * p->waves / 8);
     int nks = 256 / nblk;
     if (nks > nkt) nks = nkt;

@@ -68,6 +68,7 @@ def test_invalid_plans_are_rejected():
         assert cg.codegemm_workspace_bytes(d, p) > 0
     d3 = cg.Desc.make(4, 512, 512, 8, 3)
     assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(16, 2, 1, 4)) == 0    # 4 rows x 3 codebooks x 16 rows per lane
+    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(8, 2, 1, 4)) == 0
     assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(16, 1, 1, 4)) > 0
 
 

@@ -58,7 +58,7 @@ def plan_ok(waves, row_words, m, bg=1):
     if row_words == 4:
         return waves == 16 and bg == 1 and m <= 2
     if row_words == 2:
-        return bg * m <= 4
+        return bg * m <= (8 if waves == 8 else 4)
     return True
 
 
