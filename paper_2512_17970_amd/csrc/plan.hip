@@ -44,9 +44,10 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
     const int ngr = ceil_div(d->out_features, kGranuleRows);
     const int nkt = ceil_div(J, kSlots);
     p->batch_group = d->batch == 1 ? 1 : (d->batch == 2 ? 2 : 4);
-    // 512-row blocks for large matrices, 256-row blocks (more, shorter K ranges) below ~32 MB of codes
-    const double code_bytes = (double)m * d->out_features * J;
-    p->waves = (code_bytes >= 32e6 && p->batch_group * m <= 4) ? 16 : 8;
+    // 512-row blocks for large matrices with one or two codebooks, 256-row blocks (more, shorter
+    // K ranges; twice the registers per lane) otherwise -- from plan sweeps on the Llama-3 shapes
+    const double code_positions = (double)d->out_features * J;
+    p->waves = (code_positions >= 16e6 && m <= 2 && p->batch_group * m <= 4) ? 16 : 8;
     p->row_words = (p->batch_group * m <= (p->waves == 8 ? 8 : 4)) ? 2 : 1;
     const int nblk = ceil_div(ngr, p->row_words * p->waves / 8);
     int nks = 256 / nblk;
