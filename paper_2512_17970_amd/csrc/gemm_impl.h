@@ -264,14 +264,6 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
                 float* nxt = planes + (NBUF == 2 ? (par ^ 1) : 0) * (L::kBytes / 4);
                 const bool last_bb = (bb == BG - 1);
                 const bool has_next = !last_bb || u + 1 < nq;
-                if (NBUF == 2) {
-                    // build the next Psumbook of the sequence into the other buffer
-                    if (has_next) {
-                        if (last_bb) build(nxt, xr[(d + 1) % D][0]);
-                        else build(nxt, xr[d][(bb + 1) % BG]);
-                    }
-                    if (BG == 1) xr[(d + 1) % D][0] = load_x(u + 1 + D, 0);   // its slot is free again
-                }
                 // gather the current one (Step 3)
                 if (u < nq) {
                     // Opaque to the optimiser: keeps the address arithmetic on the codes
@@ -295,6 +287,15 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
                             acc[bb][q][7] += psum_at<3>(hi, off);
                         }
                     }
+                }
+                if (NBUF == 2) {
+                    // build the next Psumbook of the sequence into the other buffer (after the
+                    // gather in program order: the LDS reads that feed the accumulators go first)
+                    if (has_next) {
+                        if (last_bb) build(nxt, xr[(d + 1) % D][0]);
+                        else build(nxt, xr[d][(bb + 1) % BG]);
+                    }
+                    if (BG == 1) xr[(d + 1) % D][0] = load_x(u + 1 + D, 0);   // its slot is free again
                 }
                 if (NBUF == 1) {
                     // single buffer: everyone must be done reading before it is rebuilt
