@@ -105,18 +105,44 @@ __device__ __forceinline__ float dpp_add(float v)
     return v + __builtin_bit_cast(float, moved);
 }
 
-// Sum over the 32 lanes of each half-wavefront, on the vector ALU only (no LDS round
-// trips): four rotate-and-add steps make every lane of a 16-lane row hold the row's sum,
-// then lane 15 of rows 0 and 2 is broadcast into rows 1 and 3.  Valid in lanes 16..31
-// and 48..63.  The order of the additions is fixed.
-__device__ __forceinline__ float halfwave_sum(float v)
+// One halving step of a transposing reduction: lanes are paired by the DPP control; the
+// lane whose `upper` flag is set keeps the upper half of its n values, the other lane the
+// lower half, and each adds the partner's copy of the half it keeps.
+template <int CTRL, int N>
+__device__ __forceinline__ void halve(float (&v)[N], bool upper)
 {
-    v = dpp_add<0x128, 0xf>(v);   // row_ror:8
-    v = dpp_add<0x124, 0xf>(v);   // row_ror:4
-    v = dpp_add<0x122, 0xf>(v);   // row_ror:2
-    v = dpp_add<0x121, 0xf>(v);   // row_ror:1
-    v = dpp_add<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
-    return v;
+#pragma unroll
+    for (int i = 0; i < N / 2; ++i) {
+        const float keep = upper ? v[i + N / 2] : v[i];
+        const float send = upper ? v[i] : v[i + N / 2];
+        const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), CTRL, 0xf, 0xf, false);
+        v[i] = keep + __builtin_bit_cast(float, moved);
+    }
+}
+
+// Sums NV (8 or 16) per-lane values over the 32 lanes of each half-wavefront.  On return
+// lane l holds, in v[0], the total of value number l % NV.  Within a 16-lane row the lanes
+// are paired by rotate-8, half-mirror, and two quad permutes (vector ALU only); each step
+// halves the number of values a lane carries, so the whole reduction costs about 3*NV
+// instructions instead of 5*NV.  The two rows of a half-wavefront are then added with one
+// cross-lane shuffle.  The order of the additions is fixed.
+template <int NV>
+__device__ __forceinline__ float halfwave_transpose_sum(float (&v)[NV], int lane)
+{
+    static_assert(NV == 8 || NV == 16, "8 or 16 values");
+    if constexpr (NV == 16) {
+        halve<0x128, 16>(v, (lane & 8) != 0);              // row_ror:8
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = dpp_add<0x128, 0xf>(v[i]);
+    }
+    float (&v8)[8] = reinterpret_cast<float (&)[8]>(v);
+    halve<0x141, 8>(v8, (lane & 4) != 0);                  // row_half_mirror: l <-> l ^ 7
+    float (&v4)[4] = reinterpret_cast<float (&)[4]>(v);
+    halve<0x4e, 4>(v4, (lane & 2) != 0);                   // quad_perm [2,3,0,1]: l <-> l ^ 2
+    float (&v2)[2] = reinterpret_cast<float (&)[2]>(v);
+    halve<0xb1, 2>(v2, (lane & 1) != 0);                   // quad_perm [1,0,3,2]: l <-> l ^ 1
+    return v[0] + __shfl_xor(v[0], 16, kWave);
 }
 
 template <int M, int V, int NW, int RPL, int BG, int D>
@@ -319,28 +345,28 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
     }
     CG_STAMP(4);
 
-    // Sum over the 32 slots (lanes) of each half-wavefront; lane 16 of the half-wavefront
-    // parks the 8 totals of each of its RPL row groups in LDS (the Psumbook is no longer
-    // needed), indexed by the row's position inside the workgroup's block, so that the
-    // global stores and loads below are coalesced over all threads.
+    // Sum over the 32 slots (lanes) of each half-wavefront; the totals are parked in LDS
+    // (the Psumbook is no longer needed), indexed by the row's position inside the
+    // workgroup's block, so that the global stores and loads below are coalesced over all
+    // threads.
     constexpr int ROWS = GPW * kGranuleRows;                          // rows of this workgroup's block
     constexpr int NT = NW * kWave;
     constexpr int PER_THREAD = (BG * ROWS + NT - 1) / NT;             // outputs per thread
     float* stage = planes;                                           // [BG][ROWS]
+    {
+        constexpr int NV = (RPL == 1) ? 8 : 16;                      // values reduced together
+        const int idx = lane & (NV - 1);                             // value this lane ends up holding
 #pragma unroll
-    for (int q = 0; q < RPL; ++q) {
-        const int local = (q * (NW / 8) + wave / 8) * kGranuleRows + ((wave % 8) * 2 + khalf) * kRowsPerLane;
+        for (int q0 = 0; q0 < RPL; q0 += NV / 8) {
+            const int q = q0 + idx / 8;
+            const int local = (q * (NW / 8) + wave / 8) * kGranuleRows + ((wave % 8) * 2 + khalf) * kRowsPerLane + idx % 8;
 #pragma unroll
-        for (int bb = 0; bb < BG; ++bb) {
-            float4_t lo, hi;
+            for (int bb = 0; bb < BG; ++bb) {
+                float v[NV];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                lo[r] = halfwave_sum(acc[bb][q][r]);
-                hi[r] = halfwave_sum(acc[bb][q][4 + r]);
-            }
-            if ((lane & 31) == 16) {
-                *reinterpret_cast<float4_t*>(stage + bb * ROWS + local) = lo;
-                *reinterpret_cast<float4_t*>(stage + bb * ROWS + local + 4) = hi;
+                for (int i = 0; i < NV; ++i) v[i] = acc[bb][q0 + i / 8][i % 8];
+                const float t = halfwave_transpose_sum<NV>(v, lane);
+                if ((lane & 31) < NV) stage[bb * ROWS + local] = t;
             }
         }
     }
