@@ -188,12 +188,13 @@ def psumbook_bench(torch, cg, synth):
                     f"{P.numel() * 4 / us * 1e-3:.0f} GB/s written, {2 * macs / us * 1e-6:.2f} TFLOP/s")
 
 
-def read_traffic():
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", "gemm_kernel_c3_pmc.txt")
+def read_traffic(key):
+    """HBM bytes per launch of this workload (mean over its gemm_kernel launches) from the
+    committed rocprofv3 --pmc summary, if it covers the workload."""
+    path = os.path.join(ROOT, "profiles", "gemm_kernel_hbm_traffic_pmc.txt")
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch="):
+            if line.startswith(f"traffic_bytes_per_launch_{key}="):
                 return float(line.split("=", 1)[1])
     except OSError:
         pass
@@ -248,7 +249,7 @@ def main():
     value = step_bytes / (ms_per_step * 1e-3) * 1e-9
     us_per_launch = ms * 1e3 / launches
     roofline = {"bound": "hbm", "achieved": value, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": value / HBM_PEAK_GBPS, "traffic": read_traffic(),
+                "frac": value / HBM_PEAK_GBPS, "traffic": read_traffic(key),
                 "kernel": "cg::gemm_kernel", "avg_launch_us": us_per_launch,
                 "algorithmic_bytes_per_launch": step_bytes / len(layers)}
     out = {
