@@ -27,9 +27,10 @@ struct Geometry {
     int B, K, N, v, m, J;
     int NW;         // wavefronts per workgroup (8 or 16)
     int RPL;        // 8-row words per lane per unit (1, 2 or 4): the workgroup owns 16 * NW * RPL rows
+                    // (32 * NW * RPL in the batched kernel, BG = 4)
     int BG;         // batch rows per pass over the codes
     int NGR;        // ceil(N / 128) granules
-    int NBLK;       // row blocks = workgroups along N: ceil(NGR / (RPL * NW / 8))
+    int NBLK;       // row blocks = workgroups along N: NGR over the granules per workgroup, rounded up
     int NKT;        // ceil(J / 32) K tiles
     int NKS;        // workgroups per row block (K ranges)
     int KPW;        // K tiles per workgroup: ceil(NKT / NKS)

@@ -3,7 +3,7 @@
 #include <utility>
 #include <vector>
 
-#include "gemm_impl.h"
+#include "gemm_batch_impl.h"
 
 namespace cg {
 
@@ -65,6 +65,15 @@ extern "C" int codegemm_gemm(const codegemm_desc* desc, const codegemm_plan* pla
     p.trace = g_trace;
 #endif
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (g.BG == 4) {
+        switch (g.m) {
+            case 1: return launch_gemm_batch_m1(g, p, s);
+            case 2: return launch_gemm_batch_m2(g, p, s);
+            case 3: return launch_gemm_batch_m3(g, p, s);
+            case 4: return launch_gemm_batch_m4(g, p, s);
+        }
+        return CODEGEMM_UNSUPPORTED;
+    }
     switch (g.m) {
         case 1: return launch_gemm_m1(g, p, s);
         case 2: return launch_gemm_m2(g, p, s);

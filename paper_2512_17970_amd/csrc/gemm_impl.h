@@ -21,9 +21,9 @@
 //     no workgroup ever talks to another.  With k_splits > 1 each workgroup writes one
 //     fp32 partial per row to the workspace and the last one to finish a row block
 //     (atomic ticket) adds the partials in range order, scales and stores y.
-// Batch rows are processed in groups of BG (1, 2 or 4) per pass over the codes: the
-// code words in registers are reused for the BG Psumbooks of a unit; groups are
-// separate workgroups (grid.z).
+// Batch rows are processed in groups of BG (1 or 2) per pass over the codes: the code
+// words in registers are reused for the BG Psumbooks of a unit; groups are separate
+// workgroups (grid.z).  Groups of 4 have a kernel of their own (gemm_batch_impl.h).
 //
 // LDS layout of one Psumbook buffer.  Rows of 256 bytes, one per centroid index,
 // holding the 32 slots of two codebooks (codebook c: byte offset 128*(c%2)), grouped
@@ -143,6 +143,105 @@ __device__ __forceinline__ float halfwave_transpose_sum(float (&v)[NV], int lane
     float (&v2)[2] = reinterpret_cast<float (&)[2]>(v);
     halve<0xb1, 2>(v2, (lane & 1) != 0);                   // quad_perm [1,0,3,2]: l <-> l ^ 1
     return v[0] + __shfl_xor(v[0], 16, kWave);
+}
+
+// End of a workgroup's work, shared by the gather kernels.  `stage` (LDS) holds the
+// workgroup's BG x ROWS row totals over its K range.  With one K range they are scaled and
+// stored.  Otherwise each workgroup stores its totals as fp32 partials, takes a ticket on
+// the row block's counter, and the last one to arrive adds the partials of all K ranges in
+// range order, scales and stores y.  Ends with the kernel: every path returns.
+template <int NT, int BG, int ROWS>
+__device__ __forceinline__ void finish_block(const GemmParams& p, const float* stage, uint32_t* flag,
+                                             int tid, int blk, int ks, int b0)
+{
+    CG_STAMP(9);
+    __syncthreads();
+    CG_STAMP(10);
+
+    constexpr int PER_THREAD = (BG * ROWS + NT - 1) / NT;             // outputs per thread
+    const int n_base = blk * ROWS;
+    float mine[PER_THREAD];
+    _Float16 scale[PER_THREAD];
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+        const int o = tid + i * NT;
+        const int nn = n_base + o % ROWS;
+        mine[i] = (o < BG * ROWS) ? stage[o] : 0.0f;
+        scale[i] = p.scales[nn < p.N ? nn : 0];                      // requested before any ticket round trip
+    }
+    auto store_y = [&](int row, int nn, float val) {
+        if (p.y_fp32) static_cast<float*>(p.y)[(size_t)row * p.N + nn] = val;
+        else static_cast<_Float16*>(p.y)[(size_t)row * p.N + nn] = (_Float16)val;
+    };
+
+    if (p.NKS == 1) {
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) {
+            const int o = tid + i * NT;
+            const int row = b0 + o / ROWS, nn = n_base + o % ROWS;
+            if (o < BG * ROWS && row < p.B && nn < p.N) store_y(row, nn, mine[i] * (float)scale[i]);
+        }
+        CG_STAMP(3);
+        return;
+    }
+
+    // K ranges are combined through the workspace.  Every datum that crosses workgroups
+    // is moved by device-scope atomic accesses (write-through stores, cache-bypassing
+    // loads, one RMW on the counter), so no L2 write-back / invalidate is needed: each
+    // thread waits for its own partial stores to be acknowledged, the barrier collects
+    // that for the workgroup, and only then is the ticket taken.
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+        const int o = tid + i * NT;
+        const int row = b0 + o / ROWS, nn = n_base + o % ROWS;
+        if (o < BG * ROWS && row < p.B && nn < p.Npad)
+            __hip_atomic_store(p.partials + ((size_t)row * p.NKS + ks) * p.Npad + nn, mine[i],
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    CG_STAMP(5);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    CG_STAMP(6);
+    if (tid == 0) {
+        uint32_t* ctr = p.counters + (size_t)blockIdx.z * gridDim.y + blk;
+        const uint32_t old = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = old == (uint32_t)(p.NKS - 1);
+        if (last) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+        *flag = last ? 1u : 0u;
+    }
+    __syncthreads();
+    CG_STAMP(7);
+    if (*flag == 0u) return;
+    // Last workgroup of this row block: add the partials of all K ranges in range order.
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+        const int o = tid + i * NT;
+        const int row = b0 + o / ROWS, nn = n_base + o % ROWS;
+        if (o >= BG * ROWS || row >= p.B || nn >= p.N) continue;
+        const float* src = p.partials + (size_t)row * p.NKS * p.Npad + nn;
+        float sum = 0.0f;
+        int k2 = 0;
+        for (; k2 + 8 <= p.NKS; k2 += 8) {              // 8 loads in flight, added in range order
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                v[j] = __hip_atomic_load(src + (size_t)(k2 + j) * p.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) sum += v[j];
+        }
+        for (; k2 + 4 <= p.NKS; k2 += 4) {
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                v[j] = __hip_atomic_load(src + (size_t)(k2 + j) * p.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sum += v[j];
+        }
+        for (; k2 < p.NKS; ++k2)
+            sum += __hip_atomic_load(src + (size_t)k2 * p.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        store_y(row, nn, sum * (float)scale[i]);
+    }
+    CG_STAMP(3);
 }
 
 template <int M, int V, int NW, int RPL, int BG, int D>
@@ -350,8 +449,6 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
     // workgroup's block, so that the global stores and loads below are coalesced over all
     // threads.
     constexpr int ROWS = GPW * kGranuleRows;                          // rows of this workgroup's block
-    constexpr int NT = NW * kWave;
-    constexpr int PER_THREAD = (BG * ROWS + NT - 1) / NT;             // outputs per thread
     float* stage = planes;                                           // [BG][ROWS]
     {
         constexpr int NV = (RPL == 1) ? 8 : 16;                      // values reduced together
@@ -370,93 +467,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
             }
         }
     }
-    CG_STAMP(9);
-    __syncthreads();
-    CG_STAMP(10);
-
-    const int n_base = blk * ROWS;
-    float mine[PER_THREAD];
-    _Float16 scale[PER_THREAD];
-#pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
-        const int o = tid + i * NT;
-        const int nn = n_base + o % ROWS;
-        mine[i] = (o < BG * ROWS) ? stage[o] : 0.0f;
-        scale[i] = p.scales[nn < p.N ? nn : 0];                      // requested before any ticket round trip
-    }
-    auto store_y = [&](int row, int nn, float val) {
-        if (p.y_fp32) static_cast<float*>(p.y)[(size_t)row * p.N + nn] = val;
-        else static_cast<_Float16*>(p.y)[(size_t)row * p.N + nn] = (_Float16)val;
-    };
-
-    if (p.NKS == 1) {
-#pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            const int o = tid + i * NT;
-            const int row = b0 + o / ROWS, nn = n_base + o % ROWS;
-            if (o < BG * ROWS && row < p.B && nn < p.N) store_y(row, nn, mine[i] * (float)scale[i]);
-        }
-        CG_STAMP(3);
-        return;
-    }
-
-    // K ranges are combined through the workspace.  Every datum that crosses workgroups
-    // is moved by device-scope atomic accesses (write-through stores, cache-bypassing
-    // loads, one RMW on the counter), so no L2 write-back / invalidate is needed: each
-    // thread waits for its own partial stores to be acknowledged, the barrier collects
-    // that for the workgroup, and only then is the ticket taken.
-#pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
-        const int o = tid + i * NT;
-        const int row = b0 + o / ROWS, nn = n_base + o % ROWS;
-        if (o < BG * ROWS && row < p.B && nn < p.Npad)
-            __hip_atomic_store(p.partials + ((size_t)row * p.NKS + ks) * p.Npad + nn, mine[i],
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    CG_STAMP(5);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    CG_STAMP(6);
-    if (tid == 0) {
-        uint32_t* ctr = p.counters + (size_t)blockIdx.z * gridDim.y + blk;
-        const uint32_t old = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const bool last = old == (uint32_t)(p.NKS - 1);
-        if (last) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
-        *flag = last ? 1u : 0u;
-    }
-    __syncthreads();
-    CG_STAMP(7);
-    if (*flag == 0u) return;
-    // Last workgroup of this row block: add the partials of all K ranges in range order.
-#pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
-        const int o = tid + i * NT;
-        const int row = b0 + o / ROWS, nn = n_base + o % ROWS;
-        if (o >= BG * ROWS || row >= p.B || nn >= p.N) continue;
-        const float* src = p.partials + (size_t)row * p.NKS * p.Npad + nn;
-        float sum = 0.0f;
-        int k2 = 0;
-        for (; k2 + 8 <= p.NKS; k2 += 8) {              // 8 loads in flight, added in range order
-            float v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                v[j] = __hip_atomic_load(src + (size_t)(k2 + j) * p.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) sum += v[j];
-        }
-        for (; k2 + 4 <= p.NKS; k2 += 4) {
-            float v[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                v[j] = __hip_atomic_load(src + (size_t)(k2 + j) * p.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) sum += v[j];
-        }
-        for (; k2 < p.NKS; ++k2)
-            sum += __hip_atomic_load(src + (size_t)k2 * p.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        store_y(row, nn, sum * (float)scale[i]);
-    }
-    CG_STAMP(3);
+    finish_block<NW * kWave, BG, ROWS>(p, stage, flag, tid, blk, ks, b0);
 }
 
 int set_max_lds(const void* fn, size_t bytes);
@@ -500,13 +511,11 @@ int launch_gemm_m(const Geometry& g, const GemmParams& p, hipStream_t stream)
         switch (g.BG) {
             case 1: return launch_gemm_mvb<M, 8, 1>(g, p, stream);
             case 2: return launch_gemm_mvb<M, 8, 2>(g, p, stream);
-            case 4: return launch_gemm_mvb<M, 8, 4>(g, p, stream);
         }
     } else {
         switch (g.BG) {
             case 1: return launch_gemm_mvb<M, 4, 1>(g, p, stream);
             case 2: return launch_gemm_mvb<M, 4, 2>(g, p, stream);
-            case 4: return launch_gemm_mvb<M, 4, 4>(g, p, stream);
         }
     }
     return CODEGEMM_UNSUPPORTED;

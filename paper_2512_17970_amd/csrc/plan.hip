@@ -26,6 +26,11 @@ static int validate_plan(const codegemm_desc* d, const codegemm_plan* p)
     for (int i = 0; i < 4; ++i)
         if (p->reserved[i]) return CODEGEMM_INVALID_ARG;
     const int m = d->num_codebooks;
+    if (p->batch_group == 4) {
+        // the batched kernel: 32 accumulators per row word
+        if (p->row_words == 4 || (p->row_words == 2 && p->waves != 8)) return CODEGEMM_UNSUPPORTED;
+        return CODEGEMM_OK;
+    }
     if (p->row_words >= 2 && p->batch_group * m > (p->waves == 8 ? 8 : 4)) return CODEGEMM_UNSUPPORTED;   // accumulators + code ring must fit in registers
     if (p->row_words == 4 && (p->batch_group != 1 || m > 2)) return CODEGEMM_UNSUPPORTED;
     return CODEGEMM_OK;
@@ -44,6 +49,18 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
     const int ngr = ceil_div(d->out_features, kGranuleRows);
     const int nkt = ceil_div(J, kSlots);
     p->batch_group = d->batch == 1 ? 1 : (d->batch == 2 ? 2 : 4);
+    if (p->batch_group == 4) {
+        // LDS- and ALU-bound: 512-row blocks; K ranges cut so that all batch groups together
+        // give close to, but not more than, 256 workgroups
+        p->waves = 16;
+        p->row_words = 1;
+        const int nblk4 = ceil_div(ngr, 4) * ceil_div(d->batch, 4);
+        int nks4 = 256 / nblk4;
+        if (nks4 > nkt) nks4 = nkt;
+        if (nks4 < 1) nks4 = 1;
+        p->k_splits = ceil_div(nkt, ceil_div(nkt, nks4));
+        return;
+    }
     // 512-row blocks for large matrices with one or two codebooks, 256-row blocks (more, shorter
     // K ranges; twice the registers per lane) otherwise -- from plan sweeps on the Llama-3 shapes
     const double code_positions = (double)d->out_features * J;
@@ -78,7 +95,7 @@ int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g
     g->RPL = plan->row_words;
     g->BG = plan->batch_group;
     g->NGR = ceil_div(g->N, kGranuleRows);
-    g->NBLK = ceil_div(g->NGR, g->RPL * g->NW / 8);
+    g->NBLK = ceil_div(g->NGR, g->RPL * g->NW / (g->BG == 4 ? 4 : 8));
     g->NKT = ceil_div(g->J, kSlots);
     int nks = plan->k_splits < g->NKT ? plan->k_splits : g->NKT;
     g->KPW = ceil_div(g->NKT, nks);

@@ -43,7 +43,8 @@ def test_default_plans_are_valid_for_all_workloads():
             ngr = -(-c.N // 128)
             nkt = -(-c.J // 32)
             assert p.row_words in (1, 2, 4)
-            nblk = -(-ngr // (p.row_words * p.waves // 8))
+            gpw = p.row_words * p.waves // (4 if p.batch_group == 4 else 8)      # granules per workgroup
+            nblk = -(-ngr // gpw) * (-(-c.B // p.batch_group) if p.batch_group == 4 else 1)
             assert 1 <= p.k_splits <= nkt and nblk * p.k_splits <= max(256, nblk)
             assert cg.codegemm_packed_codes_bytes(d) == ngr * 128 * nkt * 32 * c.m
             assert cg.codegemm_workspace_bytes(d) >= c.B * p.k_splits * ngr * 128 * 4
@@ -67,9 +68,11 @@ def test_invalid_plans_are_rejected():
     for p in (cg.Plan.make(8, 1, 1), cg.Plan.make(16, 2, 4, 2), cg.Plan.make(8, 1, 100000, 4), cg.Plan.make(16, 4, 2)):
         assert cg.codegemm_workspace_bytes(d, p) > 0
     d3 = cg.Desc.make(4, 512, 512, 8, 3)
-    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(16, 2, 1, 4)) == 0    # 4 rows x 3 codebooks x 16 rows per lane
-    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(8, 2, 1, 4)) == 0
+    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(16, 2, 1, 4)) == 0    # batched kernel: 64 accumulators need 8-wavefront workgroups
+    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(8, 4, 1, 4)) == 0
+    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(8, 2, 1, 4)) > 0
     assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(16, 1, 1, 4)) > 0
+    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(16, 2, 1, 2)) == 0    # 2 rows x 3 codebooks x 16 rows per lane
 
 
 def test_compressed_bytes_closed_form():
