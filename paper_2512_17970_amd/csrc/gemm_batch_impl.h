@@ -73,7 +73,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be: keeps buffer descriptors in scalar registers
     const int ks = blockIdx.x;
     const int blk = blockIdx.y;                        // row block of GPW granules
     const int b0 = blockIdx.z * BG;
