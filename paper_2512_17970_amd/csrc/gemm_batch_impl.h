@@ -215,7 +215,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
             const int t = t0 + d;
             const int par = (NBUF == 2) ? (d & 1) : 0;
             float* nxt = planes + (NBUF == 2 ? (par ^ 1) : 0) * (L::kBytes / 4);
-            if (t < ntiles) {
+            auto gather = [&]() {
 #pragma unroll
                 for (int q = 0; q < RPL; ++q) {
 #pragma unroll
@@ -242,8 +242,9 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
                         }
                     }
                 }
-            }
-            if (NBUF == 1) __syncthreads();            // single buffer: everyone is done reading before it is rebuilt
+            };
+            if (t < ntiles) gather();
+            if (NBUF == 1) __syncthreads();                // single buffer: everyone is done reading before it is rebuilt
             if (t + 1 < ntiles) build(nxt, xr[(d + 1) % D]);
 #pragma unroll
             for (int i = 0; i < XN; ++i) xr[(d + 1) % D][i] = load_x(t + 1 + D, i);   // its ring slot is free again
@@ -293,13 +294,17 @@ template <int M>
 int launch_gemm_batch_m(const Geometry& g, const GemmParams& p, hipStream_t stream)
 {
     if (g.v == 8) {
-        if (g.NW == 16 && g.RPL == 1) return launch_gemm_batch_one<M, 8, 16, 1, 8>(g, p, stream);
+        if (g.NW == 16 && g.RPL == 1) return launch_gemm_batch_one<M, 8, 16, 1, 4>(g, p, stream);
         if (g.NW == 8 && g.RPL == 1) return launch_gemm_batch_one<M, 8, 8, 1, 8>(g, p, stream);
         if (g.NW == 8 && g.RPL == 2) return launch_gemm_batch_one<M, 8, 8, 2, 8>(g, p, stream);
+        if (g.NW == 8 && g.RPL == 4) return launch_gemm_batch_one<M, 8, 8, 4, 4>(g, p, stream);
+        if (g.NW == 16 && g.RPL == 2) return launch_gemm_batch_one<M, 8, 16, 2, 2>(g, p, stream);
     } else {
-        if (g.NW == 16 && g.RPL == 1) return launch_gemm_batch_one<M, 4, 16, 1, 8>(g, p, stream);
+        if (g.NW == 16 && g.RPL == 1) return launch_gemm_batch_one<M, 4, 16, 1, 4>(g, p, stream);
         if (g.NW == 8 && g.RPL == 1) return launch_gemm_batch_one<M, 4, 8, 1, 8>(g, p, stream);
         if (g.NW == 8 && g.RPL == 2) return launch_gemm_batch_one<M, 4, 8, 2, 8>(g, p, stream);
+        if (g.NW == 8 && g.RPL == 4) return launch_gemm_batch_one<M, 4, 8, 4, 4>(g, p, stream);
+        if (g.NW == 16 && g.RPL == 2) return launch_gemm_batch_one<M, 4, 16, 2, 2>(g, p, stream);
     }
     return CODEGEMM_UNSUPPORTED;
 }

@@ -20,7 +20,7 @@ static int validate_plan(const codegemm_desc* d, const codegemm_plan* p)
 {
     if (p->waves != 8 && p->waves != 16) return CODEGEMM_UNSUPPORTED;
     if (p->row_words != 1 && p->row_words != 2 && p->row_words != 4) return CODEGEMM_UNSUPPORTED;
-    if (p->row_words == 4 && p->waves != 16) return CODEGEMM_UNSUPPORTED;
+    if (p->row_words == 4 && p->waves != 16 && p->batch_group != 4) return CODEGEMM_UNSUPPORTED;
     if (p->k_splits < 1) return CODEGEMM_UNSUPPORTED;
     if (p->batch_group != 1 && p->batch_group != 2 && p->batch_group != 4) return CODEGEMM_UNSUPPORTED;
     for (int i = 0; i < 4; ++i)
@@ -28,7 +28,7 @@ static int validate_plan(const codegemm_desc* d, const codegemm_plan* p)
     const int m = d->num_codebooks;
     if (p->batch_group == 4) {
         // the batched kernel: 32 accumulators per row word
-        if (p->row_words == 4 || (p->row_words == 2 && p->waves != 8)) return CODEGEMM_UNSUPPORTED;
+        if (p->row_words == 4 && p->waves != 8) return CODEGEMM_UNSUPPORTED;
         return CODEGEMM_OK;
     }
     if (p->row_words >= 2 && p->batch_group * m > (p->waves == 8 ? 8 : 4)) return CODEGEMM_UNSUPPORTED;   // accumulators + code ring must fit in registers
@@ -50,11 +50,14 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
     const int nkt = ceil_div(J, kSlots);
     p->batch_group = d->batch == 1 ? 1 : (d->batch == 2 ? 2 : 4);
     if (p->batch_group == 4) {
-        // LDS- and ALU-bound: 512-row blocks; K ranges cut so that all batch groups together
-        // give close to, but not more than, 256 workgroups
+        // LDS- and ALU-bound.  Every workgroup rebuilds the Psumbook of its tiles, and LDS
+        // writes are slow, so blocks are 1024 rows tall when there are at least two batch
+        // groups to fill the chip with, 512 otherwise; K ranges are cut so that all batch
+        // groups together give close to, but not more than, 256 workgroups.
+        const int groups = ceil_div(d->batch, 4);
         p->waves = 16;
-        p->row_words = 1;
-        const int nblk4 = ceil_div(ngr, 4) * ceil_div(d->batch, 4);
+        p->row_words = groups >= 2 ? 2 : 1;
+        const int nblk4 = ceil_div(ngr, 4 * p->row_words) * groups;
         int nks4 = 256 / nblk4;
         if (nks4 > nkt) nks4 = nkt;
         if (nks4 < 1) nks4 = 1;

@@ -68,8 +68,9 @@ def test_invalid_plans_are_rejected():
     for p in (cg.Plan.make(8, 1, 1), cg.Plan.make(16, 2, 4, 2), cg.Plan.make(8, 1, 100000, 4), cg.Plan.make(16, 4, 2)):
         assert cg.codegemm_workspace_bytes(d, p) > 0
     d3 = cg.Desc.make(4, 512, 512, 8, 3)
-    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(16, 2, 1, 4)) == 0    # batched kernel: 64 accumulators need 8-wavefront workgroups
-    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(8, 4, 1, 4)) == 0
+    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(16, 4, 1, 4)) == 0    # batched kernel: 128 accumulators need 8-wavefront workgroups
+    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(8, 4, 1, 4)) > 0
+    assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(16, 2, 1, 4)) > 0
     assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(8, 2, 1, 4)) > 0
     assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(16, 1, 1, 4)) > 0
     assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(16, 2, 1, 2)) == 0    # 2 rows x 3 codebooks x 16 rows per lane

@@ -56,7 +56,7 @@ def test_tiny_config(y_fp32):
 
 def plan_ok(waves, row_words, m, bg=1):
     if bg == 4:                                   # the batched kernel
-        return row_words == 1 or (row_words == 2 and waves == 8)
+        return row_words <= 2 or waves == 8
     if row_words == 4:
         return waves == 16 and bg == 1 and m <= 2
     if row_words == 2:
@@ -78,7 +78,8 @@ def test_every_plan_shape(v, m, k_splits, waves, row_words):
 @pytest.mark.parametrize("v,m,waves,row_words,k_splits", [(8, 2, 8, 1, 2), (8, 2, 16, 2, 1), (4, 1, 8, 2, 1), (8, 3, 16, 1, 2),
                                                           (8, 1, 16, 2, 3), (8, 2, 16, 1, 3), (4, 1, 16, 1, 1), (8, 1, 8, 1, 2),
                                                           (8, 3, 8, 2, 1), (4, 3, 8, 1, 3), (8, 4, 16, 1, 2), (4, 4, 8, 2, 1),
-                                                          (4, 2, 8, 2, 2)])
+                                                          (4, 2, 8, 2, 2), (8, 2, 16, 2, 2), (8, 2, 8, 4, 1), (4, 1, 8, 4, 2),
+                                                          (8, 3, 16, 2, 1), (4, 4, 8, 4, 3)])
 def test_batch_groups(B, bg, v, m, waves, row_words, k_splits):
     if not plan_ok(waves, row_words, m, bg):
         pytest.skip("plan not offered for this m and batch group")
@@ -89,7 +90,8 @@ def test_batch_groups(B, bg, v, m, waves, row_words, k_splits):
 def test_batched_kernel_long_ragged_k():
     """Batch groups of 4 over a long K range with a ragged last unit and a ragged last row block."""
     for (v, m, waves, rw, splits, B) in [(8, 2, 16, 1, 1, 4), (8, 2, 8, 2, 2, 9), (4, 1, 16, 1, 1, 6), (8, 1, 8, 1, 3, 4),
-                                         (8, 3, 8, 1, 1, 5), (8, 4, 16, 1, 2, 8), (4, 2, 8, 2, 1, 32)]:
+                                         (8, 3, 8, 1, 1, 5), (8, 4, 16, 1, 2, 8), (4, 2, 8, 2, 1, 32), (8, 2, 16, 2, 1, 7), (8, 1, 8, 4, 2, 4),
+                                         (8, 4, 16, 2, 3, 12)]:
         case = synth.custom_case(v * (32 * 21 + 5), 700, v, m, B, seed=96)
         run_case(case, plan=cg.Plan.make(waves, rw, splits, 4), dequant=False)
 
