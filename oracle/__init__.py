@@ -6,7 +6,8 @@ imports the other.
 
     build()                       compile codegemm_oracle.c with gcc (+OpenMP)
     gemm(x, codes, codebooks, scales)        -> (y, T)  float64 [B][N]
-    dequantize(codes, codebooks, scales, K)  -> W       float64 [N][K]
+    dequantize(codes, codebooks, scales)     -> W       float64 [N][K]
+scales is [N] (one scale per output row, g = -1) or [N][K/g] (one per run of g weights).
     psumbook(x, codebooks)                   -> P       float64 [B][m][K/v][256]
 """
 from __future__ import annotations
@@ -41,9 +42,9 @@ def _load() -> ctypes.CDLL:
         lib = ctypes.CDLL(_LIB)
         i, p = ctypes.c_int, ctypes.c_void_p
         lib.oracle_num_threads.restype = i
-        lib.oracle_dequantize.argtypes = [i, i, i, i, p, p, p, p]
+        lib.oracle_dequantize.argtypes = [i, i, i, i, i, p, p, p, p]
         lib.oracle_dequantize.restype = i
-        lib.oracle_gemm.argtypes = [i, i, i, i, i, p, p, p, p, p, p]
+        lib.oracle_gemm.argtypes = [i, i, i, i, i, i, p, p, p, p, p, p]
         lib.oracle_gemm.restype = i
         lib.oracle_psumbook.argtypes = [i, i, i, i, p, p, p]
         lib.oracle_psumbook.restype = i
@@ -74,17 +75,27 @@ def _shapes(codes: np.ndarray, codebooks: np.ndarray) -> Tuple[int, int, int, in
     return m, N, J, v
 
 
+def _group_size(scales: np.ndarray, N: int, K: int) -> int:
+    """-1 for scales of shape [N]; K / G for shape [N][G]."""
+    if scales.shape == (N,):
+        return -1
+    if scales.ndim == 2 and scales.shape[0] == N and scales.shape[1] >= 1 and K % scales.shape[1] == 0:
+        return K // scales.shape[1]
+    raise ValueError("scales must be [N] or [N][K/g]")
+
+
 def gemm(x: np.ndarray, codes: np.ndarray, codebooks: np.ndarray, scales: np.ndarray):
     """y[b][n] and T[b][n] (sum of |x*W| terms), both float64."""
     x = _c(x, np.float16); codes = _c(codes, np.uint8)
     codebooks = _c(codebooks, np.float16); scales = _c(scales, np.float16)
     m, N, J, v = _shapes(codes, codebooks)
     B, K = x.shape
-    if K != J * v or scales.shape != (N,):
+    if K != J * v:
         raise ValueError("shape mismatch")
+    g = _group_size(scales, N, K)
     y = np.empty((B, N), np.float64)
     T = np.empty((B, N), np.float64)
-    rc = _load().oracle_gemm(B, N, K, v, m, _ptr(x.view(np.uint16)), _ptr(codes),
+    rc = _load().oracle_gemm(B, N, K, v, m, g, _ptr(x.view(np.uint16)), _ptr(codes),
                              _ptr(codebooks.view(np.uint16)), _ptr(scales.view(np.uint16)), _ptr(y), _ptr(T))
     if rc:
         raise RuntimeError(f"oracle_gemm failed: {rc}")
@@ -95,7 +106,8 @@ def dequantize(codes: np.ndarray, codebooks: np.ndarray, scales: np.ndarray) -> 
     codes = _c(codes, np.uint8); codebooks = _c(codebooks, np.float16); scales = _c(scales, np.float16)
     m, N, J, v = _shapes(codes, codebooks)
     W = np.empty((N, J * v), np.float64)
-    rc = _load().oracle_dequantize(N, J * v, v, m, _ptr(codes), _ptr(codebooks.view(np.uint16)),
+    g = _group_size(scales, N, J * v)
+    rc = _load().oracle_dequantize(N, J * v, v, m, g, _ptr(codes), _ptr(codebooks.view(np.uint16)),
                                    _ptr(scales.view(np.uint16)), _ptr(W))
     if rc:
         raise RuntimeError(f"oracle_dequantize failed: {rc}")

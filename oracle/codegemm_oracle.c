@@ -8,12 +8,13 @@
  *
  * What it computes, written out from the definitions (no Psumbook here):
  *
- *   W[n][v*j + k] = s[n] * sum_{c<m} C[c][ code[c][n][j] ][k]
+ *   W[n][v*j + k] = s[n][(v*j + k) / g] * sum_{c<m} C[c][ code[c][n][j] ][k]
  *       a weight vector of length v is the sum of m centroid vectors, each
  *       picked by its code (Section 2.2, additive multi-codebook paragraph);
  *       vectors are consecutive runs of v elements along K (Section 3,
- *       x^j_k = x_{v*j+k}); the row is de-normalised by its scale
- *       (Section 2.2, Step 1, with g = -1: one scale per output row).
+ *       x^j_k = x_{v*j+k}); every run of g consecutive weights of a row (g/v
+ *       vectors, g >= v) is de-normalised by its own scale (Section 2.2,
+ *       Step 1); g = -1 means one scale per output row, s[n].
  *   y[b][n] = sum_{kk<K} x[b][kk] * W[n][kk]                     (y = x W^T)
  *   T[b][n] = sum_{kk<K} | x[b][kk] * W[n][kk] |                 (sum of |terms|)
  *
@@ -23,13 +24,16 @@
  *
  * Inputs are IEEE binary16 bit patterns; each is converted exactly to double.
  * Every sum is accumulated in double in index order.  Layouts (row-major):
- *   x[B][K] u16, codes[m][N][K/v] u8, codebooks[m][256][v] u16, scales[N] u16,
+ *   x[B][K] u16, codes[m][N][K/v] u8, codebooks[m][256][v] u16,
+ *   scales[N] u16 (g = -1) or scales[N][K/g] u16 (g > 0, g a multiple of v dividing K),
  *   W[N][K] f64, y[B][N] f64, T[B][N] f64, P[B][m][K/v][256] f64.
  *
  * Pins (tests/test_oracle_*.py): exact rational brute force on tiny shapes,
  * the gather identity against a separate numpy Psumbook path, zero / one-hot /
  * +-1 codebooks (the last against an integer sign-matrix product), scale
- * linearity, row permutation, constant codes.
+ * linearity, row permutation, constant codes; for g > 0: g = K against g = -1,
+ * per-group scale linearity, exact rational brute force with groups, one group
+ * switched off against the same layer with that K range removed.
  */
 #include <math.h>
 #include <stdint.h>
@@ -72,19 +76,27 @@ static int bad_shape(int N, int K, int v, int m)
     return N < 1 || K < 1 || v < 1 || m < 1 || (K % v) != 0;
 }
 
+static int bad_group(int K, int v, int g)
+{
+    return !(g == -1 || (g >= v && (g % v) == 0 && (K % g) == 0));
+}
+
 /* One dequantized row of W, in double. */
-static void dequantize_row(int n, int N, int K, int v, int m,
-                           const uint8_t *codes, const double *cb, double scale, double *w)
+static void dequantize_row(int n, int N, int K, int v, int m, int g,
+                           const uint8_t *codes, const double *cb, const uint16_t *scales, double *w)
 {
     const int J = K / v;
     for (int j = 0; j < J; ++j) {
         for (int k = 0; k < v; ++k) {
+            const int kk = v * j + k;
+            const double scale = (g == -1) ? half_bits_to_double(scales[n])
+                                           : half_bits_to_double(scales[(size_t)n * (K / g) + kk / g]);
             double sum = 0.0;
             for (int c = 0; c < m; ++c) {
                 int code = codes[((size_t)c * N + n) * J + j];
                 sum += cb[((size_t)c * ORACLE_CENTROIDS + code) * v + k];
             }
-            w[(size_t)v * j + k] = scale * sum;
+            w[kk] = scale * sum;
         }
     }
 }
@@ -99,24 +111,24 @@ static double *codebooks_to_double(int m, int v, const uint16_t *codebooks)
 }
 
 /* W[N][K] = dequantized weight matrix. */
-int oracle_dequantize(int N, int K, int v, int m, const uint8_t *codes,
+int oracle_dequantize(int N, int K, int v, int m, int g, const uint8_t *codes,
                       const uint16_t *codebooks, const uint16_t *scales, double *W)
 {
-    if (bad_shape(N, K, v, m)) return -1;
+    if (bad_shape(N, K, v, m) || bad_group(K, v, g)) return -1;
     double *cb = codebooks_to_double(m, v, codebooks);
     if (!cb) return -2;
 #pragma omp parallel for schedule(static)
     for (int n = 0; n < N; ++n)
-        dequantize_row(n, N, K, v, m, codes, cb, half_bits_to_double(scales[n]), W + (size_t)n * K);
+        dequantize_row(n, N, K, v, m, g, codes, cb, scales, W + (size_t)n * K);
     free(cb);
     return 0;
 }
 
 /* y = x W^T and T = sum of |terms|, dequantizing one row of W at a time. */
-int oracle_gemm(int B, int N, int K, int v, int m, const uint16_t *x, const uint8_t *codes,
+int oracle_gemm(int B, int N, int K, int v, int m, int g, const uint16_t *x, const uint8_t *codes,
                 const uint16_t *codebooks, const uint16_t *scales, double *y, double *T)
 {
-    if (B < 1 || bad_shape(N, K, v, m)) return -1;
+    if (B < 1 || bad_shape(N, K, v, m) || bad_group(K, v, g)) return -1;
     double *cb = codebooks_to_double(m, v, codebooks);
     double *xd = (double *)malloc((size_t)B * K * sizeof(double));
     if (!cb || !xd) { free(cb); free(xd); return -2; }
@@ -133,7 +145,7 @@ int oracle_gemm(int B, int N, int K, int v, int m, const uint16_t *x, const uint
         if (!failed) {
 #pragma omp for schedule(static)
             for (int n = 0; n < N; ++n) {
-                dequantize_row(n, N, K, v, m, codes, cb, half_bits_to_double(scales[n]), w);
+                dequantize_row(n, N, K, v, m, g, codes, cb, scales, w);
                 for (int b = 0; b < B; ++b) {
                     const double *xb = xd + (size_t)b * K;
                     double sum = 0.0, sum_abs = 0.0;

@@ -8,7 +8,8 @@ Canonical layouts (all row-major, contiguous):
     x          [B][K]        float16   activations, N(0, 1)
     codes      [m][N][K/v]   uint8     centroid indices, uniform on 0..255
     codebooks  [m][256][v]   float16   centroids, N(0, 0.02^2)
-    scales     [N]           float16   per-output-channel scale, U[0.5, 1.5]
+    scales     [N]           float16   per-output-channel scale, U[0.5, 1.5]   (g = -1)
+               [N][K/g]      float16   one scale per run of g weights of a row   (g > 0)
 
 Draw order is fixed: codes, codebooks, scales, x.  Values are drawn in float64,
 rounded once to float16, and those float16 values are what every consumer sees.
@@ -35,6 +36,7 @@ class Case:
     m: int            # additive codebooks
     B: int            # batch
     seed: int
+    g: int = -1       # normalisation group size along K; -1 = one scale per output row
 
     @property
     def J(self) -> int:
@@ -50,14 +52,17 @@ class Inputs:
     scales: np.ndarray
 
 
-def _case(cfg: int, idx: int, K: int, N: int, v: int, m: int, B: int) -> Case:
-    return Case(name=f"c{cfg}_{K}x{N}_v{v}m{m}_b{B}", cfg=cfg, K=K, N=N, v=v, m=m, B=B,
-                seed=SEED_BASE + 100 * cfg + idx)
+def _case(cfg: int, idx: int, K: int, N: int, v: int, m: int, B: int, g: int = -1) -> Case:
+    tag = "" if g == -1 else f"g{g}"
+    return Case(name=f"c{cfg}_{K}x{N}_v{v}m{m}{tag}_b{B}", cfg=cfg, K=K, N=N, v=v, m=m, B=B,
+                seed=SEED_BASE + 100 * cfg + idx, g=g)
 
 
 def workloads() -> Dict[int, List[Case]]:
-    """The five workload families: a tiny layer, Llama-3-8B shapes (v4 m1),
-    Llama-3-70B shapes (v8 m2), a batch sweep and a bit-width sweep."""
+    """Workload families: 1 a tiny layer, 2 Llama-3-8B shapes (v4 m1), 3 Llama-3-70B
+    shapes (v8 m2), 4 a batch sweep, 5 a bit-width sweep (all with one scale per row),
+    6 a sweep of the normalisation group size g at 8192->28672, 7 and 8 the 8B and 70B
+    shapes in the formats the paper's latency table uses (m1v4g128, m2v8g128)."""
     out: Dict[int, List[Case]] = {}
     out[1] = [_case(1, 0, 512, 512, 8, 1, 1)]
     out[2] = [_case(2, i, K, N, 4, 1, 1) for i, (K, N) in
@@ -71,6 +76,13 @@ def workloads() -> Dict[int, List[Case]]:
     out[4] = c4
     out[5] = [_case(5, i, 8192, 28672, v, m, 1) for i, (v, m) in
               enumerate([(8, 1), (8, 2), (8, 3), (4, 1)])]
+    out[6] = [_case(6, i, 8192, 28672, v, m, 1, g) for i, (v, m, g) in
+              enumerate([(8, 2, 128), (8, 2, 64), (8, 2, 32), (8, 2, 16), (8, 2, 8),
+                         (4, 1, 128), (4, 1, 32), (4, 1, 4), (8, 1, 128), (8, 1, 16)])]
+    out[7] = [_case(7, i, K, N, 4, 1, 1, 128) for i, (K, N) in
+              enumerate([(4096, 4096), (4096, 1024), (4096, 14336), (14336, 4096)])]
+    out[8] = [_case(8, i, K, N, 8, 2, 1, 128) for i, (K, N) in
+              enumerate([(8192, 8192), (8192, 1024), (8192, 28672), (28672, 8192)])]
     return out
 
 
@@ -82,8 +94,9 @@ def find_case(name: str) -> Case:
     raise KeyError(name)
 
 
-def custom_case(K: int, N: int, v: int, m: int, B: int, seed: int, name: str = "") -> Case:
-    return Case(name=name or f"custom_{K}x{N}_v{v}m{m}_b{B}_s{seed}", cfg=0, K=K, N=N, v=v, m=m, B=B, seed=seed)
+def custom_case(K: int, N: int, v: int, m: int, B: int, seed: int, name: str = "", g: int = -1) -> Case:
+    tag = "" if g == -1 else f"g{g}"
+    return Case(name=name or f"custom_{K}x{N}_v{v}m{m}{tag}_b{B}_s{seed}", cfg=0, K=K, N=N, v=v, m=m, B=B, seed=seed, g=g)
 
 
 def generate(case: Case) -> Inputs:
@@ -93,7 +106,12 @@ def generate(case: Case) -> Inputs:
     rng = np.random.default_rng(case.seed)
     codes = rng.integers(0, NUM_CENTROIDS, size=(case.m, case.N, case.J), dtype=np.uint8)
     codebooks = (rng.standard_normal((case.m, NUM_CENTROIDS, case.v)) * 0.02).astype(np.float16)
-    scales = rng.uniform(0.5, 1.5, size=(case.N,)).astype(np.float16)
+    if case.g == -1:
+        scales = rng.uniform(0.5, 1.5, size=(case.N,)).astype(np.float16)
+    else:
+        if case.g < case.v or case.g % case.v or case.K % case.g:
+            raise ValueError("g must be a multiple of v that divides K")
+        scales = rng.uniform(0.5, 1.5, size=(case.N, case.K // case.g)).astype(np.float16)
     x = rng.standard_normal((case.B, case.K)).astype(np.float16)
     return Inputs(case, x, codes, codebooks, scales)
 

@@ -10,8 +10,8 @@ import synth
 from oracle.psumbook_path import psum_gemm
 
 
-def tiny(K, N, v, m, B, seed):
-    return synth.generate(synth.custom_case(K, N, v, m, B, seed))
+def tiny(K, N, v, m, B, seed, g=-1):
+    return synth.generate(synth.custom_case(K, N, v, m, B, seed, g=g))
 
 
 def frac(a):
@@ -24,8 +24,8 @@ def brute_force(inp):
     y = [[Fraction(0)] * c.N for _ in range(c.B)]
     T = [[Fraction(0)] * c.N for _ in range(c.B)]
     for n in range(c.N):
-        s = frac(inp.scales[n])
         for kk in range(c.K):
+            s = frac(inp.scales[n]) if c.g == -1 else frac(inp.scales[n, kk // c.g])
             j, k = divmod(kk, c.v)
             w = Fraction(0)
             for cb in range(c.m):
@@ -223,3 +223,86 @@ def test_rejects_bad_shapes():
     inp = tiny(32, 4, 8, 1, 1, 41)
     with pytest.raises(ValueError):
         oracle.gemm(inp.x[:, :31], inp.codes, inp.codebooks, inp.scales)
+
+
+# ---- normalisation groups along K (Section 2.2, Step 1: g/v vectors share one scale) ----
+
+@pytest.mark.parametrize("K,N,v,m,B,g", [(32, 4, 8, 1, 1, 8), (32, 3, 8, 2, 2, 16), (24, 5, 4, 1, 1, 12),
+                                        (16, 2, 4, 3, 2, 4), (64, 3, 8, 2, 1, 32)])
+def test_groups_brute_force_exact_rational(K, N, v, m, B, g):
+    inp = tiny(K, N, v, m, B, 2000 + K + g, g=g)
+    y, T = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+    yb, Tb = brute_force(inp)
+    for b in range(B):
+        for n in range(N):
+            assert abs(y[b, n] - float(yb[b][n])) <= 4e-16 * float(Tb[b][n]) * K
+            assert abs(T[b, n] - float(Tb[b][n])) <= 4e-16 * float(Tb[b][n]) * K
+
+
+@pytest.mark.parametrize("K,N,v,m,B,g", [(512, 65, 8, 2, 2, 128), (256, 33, 4, 1, 1, 32), (384, 20, 8, 3, 1, 8),
+                                        (256, 17, 4, 4, 2, 4)])
+def test_groups_gather_identity(K, N, v, m, B, g):
+    """Scaling each group's gathered partial sum equals the dequantized product."""
+    inp = tiny(K, N, v, m, B, 78, g=g)
+    y, T = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+    y2, _ = psum_gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+    assert np.all(np.abs(y - y2) <= 1e-12 * T)
+
+
+def test_one_group_per_row_is_the_row_scale():
+    """g = K is the row-wise normalisation the paper writes as g = -1."""
+    inp = tiny(64, 9, 8, 2, 2, 31)
+    y, T = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+    y2, T2 = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales.reshape(-1, 1))
+    assert np.array_equal(y, y2) and np.array_equal(T, T2)
+
+
+def test_equal_group_scales_reduce_to_row_scale():
+    inp = tiny(96, 6, 4, 2, 1, 32, g=8)
+    row = inp.scales[:, 0].copy()
+    y, _ = oracle.gemm(inp.x, inp.codes, inp.codebooks, np.repeat(row[:, None], 96 // 8, axis=1))
+    y2, T2 = oracle.gemm(inp.x, inp.codes, inp.codebooks, row)
+    assert np.all(np.abs(y - y2) <= 1e-13 * T2)
+
+
+def test_group_scale_linearity_and_locality():
+    """Doubling one group's scale adds exactly that group's contribution, which is the
+    product over that K range alone; zeroing it removes the range."""
+    K, N, v, g = 128, 7, 8, 32
+    inp = tiny(K, N, v, 2, 2, 33, g=g)
+    y, _ = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+    G = 2                                              # the third of four groups
+    lo, hi = G * g, (G + 1) * g
+    # that group's contribution, computed as a separate, smaller layer with a row-wise scale... per row
+    sub_scales = np.ascontiguousarray(inp.scales[:, G])
+    part, Tp = oracle.gemm(np.ascontiguousarray(inp.x[:, lo:hi]), np.ascontiguousarray(inp.codes[:, :, lo // v:hi // v]),
+                           inp.codebooks, sub_scales)
+    doubled = inp.scales.copy(); doubled[:, G] *= np.float16(2)
+    y2, T2 = oracle.gemm(inp.x, inp.codes, inp.codebooks, doubled)
+    assert np.all(np.abs((y2 - y) - part) <= 1e-13 * T2)
+    zeroed = inp.scales.copy(); zeroed[:, G] = 0
+    y0, _ = oracle.gemm(inp.x, inp.codes, inp.codebooks, zeroed)
+    assert np.all(np.abs((y - y0) - part) <= 1e-13 * T2)
+
+
+def test_group_boundaries_sit_at_multiples_of_g():
+    """A scale change in group G must not touch a weight just outside it: with x one-hot at
+    position kk, y is the single weight W[n][kk], which carries the scale of group kk // g."""
+    K, N, v, g = 48, 4, 4, 12
+    inp = tiny(K, N, v, 1, 1, 34, g=g)
+    W = oracle.dequantize(inp.codes, inp.codebooks, inp.scales)
+    for kk in (0, 11, 12, 23, 24, 35, 36, 47):
+        x = np.zeros((1, K), np.float16); x[0, kk] = 1
+        y, _ = oracle.gemm(x, inp.codes, inp.codebooks, inp.scales)
+        for n in range(N):
+            cent = float(inp.codebooks[0, inp.codes[0, n, kk // v], kk % v])
+            want = float(inp.scales[n, kk // g]) * cent
+            assert y[0, n] == want == W[n, kk]
+
+
+def test_rejects_bad_group_shapes():
+    inp = tiny(32, 4, 8, 1, 1, 35)
+    with pytest.raises(ValueError):
+        oracle.gemm(inp.x, inp.codes, inp.codebooks, np.ones((4, 3), np.float16))     # 32 / 3 is not whole
+    with pytest.raises(RuntimeError):
+        oracle.gemm(inp.x, inp.codes, inp.codebooks, np.ones((4, 8), np.float16))     # g = 4 < v
