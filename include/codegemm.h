@@ -4,14 +4,16 @@
  * Computes the linear layer  y = x W^T  for a weight matrix W (N x K) that is
  * stored codebook-quantized: every run of v consecutive weights along K is the
  * sum of m centroid vectors, one from each of m codebooks of 256 fp16 centroids,
- * selected by 8-bit codes, times one fp16 scale per output row
+ * selected by 8-bit codes, times an fp16 scale: one per output row (g = -1) or
+ * one per run of g consecutive weights of a row
  * (CodeGEMM paper, Section 2.2: vector length v, number of codebooks m, bits
- * per code b = 8, normalisation group g = -1).
+ * per code b = 8, normalisation group size g).
  *
  * The hot path never reconstructs W.  It builds a Psumbook (Section 3, Eq. 2)
  *     P[b][c][j][i] = sum_{k<v} C[c][i][k] * x[b][v*j + k]
  * in LDS, then gathers P by code and accumulates over j and c (Section 3,
- * Step 3), and multiplies by the row scale.
+ * Step 3), and multiplies by the row scale (g = -1) or scales every gathered
+ * partial sum by the scale of its group as it is accumulated (g > 0).
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers (HBM) unless marked "host".
@@ -28,7 +30,8 @@
  *     x          [B][K]        fp16
  *     codes      [m][N][K/v]   uint8   (every value 0..255 is a valid centroid index)
  *     codebooks  [m][256][v]   fp16
- *     scales     [N]           fp16
+ *     scales     [N]           fp16     (group_size = -1)
+ *                [N][K/g]      fp16     (group_size = g > 0)
  *     y          [B][N]        fp16, or fp32 when CODEGEMM_FLAG_Y_FP32 is set
  *     psumbook   [B][m][K/v][256] fp32
  */
@@ -62,7 +65,8 @@ typedef struct codegemm_desc {
     int32_t vec_len;        /* v: 4 or 8                                       */
     int32_t num_codebooks;  /* m: 1..4                                         */
     int32_t code_bits;      /* b: must be 8 (Section 6, Limitations)           */
-    int32_t group_size;     /* g: must be -1 (one scale per output row)        */
+    int32_t group_size;     /* g: -1 (one scale per output row), or v * 2^i    */
+                            /* (i >= 0) dividing K: one scale per g weights     */
     int32_t flags;          /* CODEGEMM_FLAG_*                                 */
 } codegemm_desc;
 
@@ -134,6 +138,20 @@ int codegemm_unpack_codes(const codegemm_desc *desc, const codegemm_plan *plan,
                           const uint8_t *packed, uint8_t *codes, void *stream);
 
 /*
+ * Scales of a layer with group_size = g > 0 (Section 2.2, Step 1), re-ordered
+ * from the canonical [N][K/g] array into the layout the gather kernels read
+ * next to the packed codes (offline, once per weight matrix).  With GPU =
+ * max(1, 32 * v / g) groups per 32-sub-vector unit, the buffer is an array
+ * [NGR][NKT][GPU][16][8] of fp16: entry (rg, kt, q, o, r) is the scale of row
+ * 128*rg + 8*o + r for the group that holds sub-vector 32*kt + q*g/v (0 when
+ * the row or the sub-vector lies outside the matrix), so the 8 rows a lane
+ * owns are one 16-byte load.  codegemm_packed_scales_bytes returns 0 for an
+ * invalid descriptor or for group_size = -1 (such layers pass scales [N] as is).
+ */
+size_t codegemm_packed_scales_bytes(const codegemm_desc *desc);
+int codegemm_pack_scales(const codegemm_desc *desc, const void *scales, void *packed, void *stream);
+
+/*
  * Section 3, Eq. 2, for the whole of K: psumbook[b][c][j][i] (fp32), from
  * x [B][K] fp16 and codebooks [m][256][v] fp16.  fp16 products are exact in
  * fp32 and are accumulated in fp32.  use_mfma != 0 computes the contraction on
@@ -145,7 +163,11 @@ int codegemm_psumbook_build(const codegemm_desc *desc, const void *x, const void
 /*
  * The hot path (Section 3, Steps 1-3, then de-normalisation by the row scale):
  *     y[b][n] = scales[n] * sum_{c<m} sum_{j<K/v} P[b][c][j][ codes[c][n][j] ].
- * `packed_codes` is the output of codegemm_pack_codes.
+ * For group_size = g > 0,
+ *     y[b][n] = sum_G scales[n][G] * sum_{c<m} sum_{j in G} P[b][c][j][ codes[c][n][j] ].
+ * `packed_codes` is the output of codegemm_pack_codes.  `scales` is the
+ * canonical [N] array when group_size = -1 and the output of
+ * codegemm_pack_scales otherwise.
  * fp16 inputs, fp32 Psumbook (built on the matrix cores: fp16 products are exact
  * in fp32) and fp32 accumulation, y rounded to nearest-even fp16 (or stored as
  * fp32 under CODEGEMM_FLAG_Y_FP32).  Every sum is taken in a fixed order (also
@@ -162,8 +184,8 @@ int codegemm_gemm(const codegemm_desc *desc, const codegemm_plan *plan,
  * Dequantization-based comparator (Section 2.3: the whole codebook sits in LDS,
  * each code fetches its centroid vector, which is multiplied with the matching
  * activations; O(N*B*K) multiply-adds).  Same result as codegemm_gemm up to
- * fp32 summation order.  `codes` is the canonical [m][N][K/v] array.  Needs no
- * workspace.
+ * fp32 summation order.  `codes` is the canonical [m][N][K/v] array and `scales`
+ * the canonical [N] or [N][K/g] array.  Needs no workspace.
  */
 int codegemm_dequant_gemm(const codegemm_desc *desc, const void *x, const uint8_t *codes,
                           const void *codebooks, const void *scales, void *y, void *stream);

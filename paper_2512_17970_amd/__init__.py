@@ -9,4 +9,6 @@ from .binding import (  # noqa: F401
     codegemm_workspace_init, codegemm_pack_codes, codegemm_unpack_codes,
     codegemm_psumbook_build, codegemm_gemm, codegemm_dequant_gemm, codegemm_status_string,
     compressed_bytes,
+    codegemm_packed_scales_bytes,
+    codegemm_pack_scales,
 )

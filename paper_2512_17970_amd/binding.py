@@ -21,6 +21,7 @@ FLAG_Y_FP32 = 1
 EXPORTS = [
     "codegemm_default_plan", "codegemm_workspace_bytes", "codegemm_packed_codes_bytes",
     "codegemm_workspace_init", "codegemm_pack_codes", "codegemm_unpack_codes",
+    "codegemm_packed_scales_bytes", "codegemm_pack_scales",
     "codegemm_psumbook_build", "codegemm_gemm", "codegemm_dequant_gemm", "codegemm_status_string",
 ]
 
@@ -83,6 +84,10 @@ def load() -> ctypes.CDLL:
     lib.codegemm_pack_codes.restype = i
     lib.codegemm_unpack_codes.argtypes = [dp, pp, vp, vp, vp]
     lib.codegemm_unpack_codes.restype = i
+    lib.codegemm_packed_scales_bytes.argtypes = [dp]
+    lib.codegemm_packed_scales_bytes.restype = sz
+    lib.codegemm_pack_scales.argtypes = [dp, vp, vp, vp]
+    lib.codegemm_pack_scales.restype = i
     lib.codegemm_psumbook_build.argtypes = [dp, vp, vp, vp, i, vp]
     lib.codegemm_psumbook_build.restype = i
     lib.codegemm_gemm.argtypes = [dp, pp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -145,6 +150,15 @@ def codegemm_unpack_codes(desc: Desc, plan: Optional[Plan], packed, codes, strea
                                         ctypes.c_void_p(stream)), "codegemm_unpack_codes")
 
 
+def codegemm_packed_scales_bytes(desc: Desc) -> int:
+    return int(load().codegemm_packed_scales_bytes(ctypes.byref(desc)))
+
+
+def codegemm_pack_scales(desc: Desc, scales, packed, stream: int = 0) -> None:
+    _check(load().codegemm_pack_scales(ctypes.byref(desc), _ptr(scales), _ptr(packed), ctypes.c_void_p(stream)),
+           "codegemm_pack_scales")
+
+
 def codegemm_psumbook_build(desc: Desc, x, codebooks, psumbook, use_mfma: bool = False, stream: int = 0) -> None:
     _check(load().codegemm_psumbook_build(ctypes.byref(desc), _ptr(x), _ptr(codebooks), _ptr(psumbook),
                                           1 if use_mfma else 0, ctypes.c_void_p(stream)), "codegemm_psumbook_build")
@@ -162,6 +176,7 @@ def codegemm_dequant_gemm(desc: Desc, x, codes, codebooks, scales, y, stream: in
                                         _ptr(y), ctypes.c_void_p(stream)), "codegemm_dequant_gemm")
 
 
-def compressed_bytes(B: int, K: int, N: int, v: int, m: int) -> int:
+def compressed_bytes(B: int, K: int, N: int, v: int, m: int, g: int = -1) -> int:
     """Bytes the method must move per call: codes + codebooks + scales + x + y (fp16 y)."""
-    return m * N * (K // v) + m * 256 * v * 2 + 2 * N + 2 * B * K + 2 * B * N
+    scales = 2 * N if g == -1 else 2 * N * (K // g)
+    return m * N * (K // v) + m * 256 * v * 2 + scales + 2 * B * K + 2 * B * N

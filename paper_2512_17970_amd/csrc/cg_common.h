@@ -36,6 +36,9 @@ struct Geometry {
     int KPW;        // K tiles per workgroup: ceil(NKT / NKS)
     int NG;         // ceil(B / BG) batch groups
     int Npad;       // NGR * 128
+    int g;          // normalisation group size along K, or -1
+    int GPU;        // scale groups per 32-sub-vector unit: max(1, 32 * v / g); 0 when g = -1
+    int gshift;     // a lane's group inside its unit = (sub-vector index in the unit) >> gshift
     bool y_fp32;
 };
 

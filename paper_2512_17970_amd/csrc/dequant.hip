@@ -23,6 +23,8 @@ struct DequantParams {
     void* y;
     int K, N, J, m, nchunks;
     int y_fp32;
+    int groups;     // scales per row: 1 (one per output row) or K / g
+    int gshift;     // sub-vector j belongs to group j >> gshift
 };
 
 __device__ __forceinline__ float wave_sum(float v)
@@ -68,6 +70,7 @@ __global__ void __launch_bounds__(kDqWaves * kWave) dequant_kernel(const Dequant
     const bool vec_ok = (p.J % 16) == 0;
     for (int n = blockIdx.x * kDqWaves + wave; n < p.N; n += gridDim.x * kDqWaves) {
         float acc = 0.0f;
+        const _Float16* srow = p.scales + (size_t)n * p.groups;
         for (int ch = 0; ch < p.nchunks; ++ch) {
             const int j0 = ch * kDqChunk + 16 * lane;
             for (int c = 0; c < p.m; ++c) {
@@ -88,16 +91,26 @@ __global__ void __launch_bounds__(kDqWaves * kWave) dequant_kernel(const Dequant
                     const uint32_t code = (cw[jj >> 2] >> (8 * (jj & 3))) & 0xffu;
                     const _Float16* cen = cb + code * V;
                     const _Float16* xv = xs + ((size_t)(ch * 16 + jj) * kWave + lane) * V;
+                    if (p.groups == 1) {
 #pragma unroll
-                    for (int h = 0; h < V / 2; ++h)
-                        acc = __builtin_amdgcn_fdot2(*reinterpret_cast<const half2_t*>(cen + 2 * h),
-                                                     *reinterpret_cast<const half2_t*>(xv + 2 * h), acc, false);
+                        for (int h = 0; h < V / 2; ++h)
+                            acc = __builtin_amdgcn_fdot2(*reinterpret_cast<const half2_t*>(cen + 2 * h),
+                                                         *reinterpret_cast<const half2_t*>(xv + 2 * h), acc, false);
+                    } else if (j0 + jj < p.J) {
+                        // group scales: the sub-vector's dot product is scaled by its group's factor
+                        float dot = 0.0f;
+#pragma unroll
+                        for (int h = 0; h < V / 2; ++h)
+                            dot = __builtin_amdgcn_fdot2(*reinterpret_cast<const half2_t*>(cen + 2 * h),
+                                                         *reinterpret_cast<const half2_t*>(xv + 2 * h), dot, false);
+                        acc = __builtin_fmaf((float)srow[(j0 + jj) >> p.gshift], dot, acc);
+                    }
                 }
             }
         }
         acc = wave_sum(acc);
         if (lane == 0) {
-            const float val = acc * (float)p.scales[n];
+            const float val = p.groups == 1 ? acc * (float)p.scales[n] : acc;
             if (p.y_fp32) static_cast<float*>(p.y)[(size_t)b * p.N + n] = val;
             else static_cast<_Float16*>(p.y)[(size_t)b * p.N + n] = (_Float16)val;
         }
@@ -128,6 +141,10 @@ extern "C" int codegemm_dequant_gemm(const codegemm_desc* desc, const void* x, c
     p.K = g.K; p.N = g.N; p.J = g.J; p.m = g.m;
     p.nchunks = ceil_div(g.J, kDqChunk);
     p.y_fp32 = g.y_fp32 ? 1 : 0;
+    p.groups = g.g > 0 ? g.K / g.g : 1;
+    p.gshift = 0;
+    if (g.g > 0)
+        while ((g.v << p.gshift) < g.g) ++p.gshift;
     const size_t lds = (size_t)g.m * kCentroids * g.v * 2 + (size_t)p.nchunks * kDqChunk * g.v * 2;
     if (lds > (size_t)kMaxLds) return CODEGEMM_UNSUPPORTED;   // x does not fit in LDS (K > ~70k)
     const void* fn = (g.v == 8) ? reinterpret_cast<const void*>(dequant_kernel<8>)

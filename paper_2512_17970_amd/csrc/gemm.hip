@@ -53,7 +53,10 @@ extern "C" int codegemm_gemm(const codegemm_desc* desc, const codegemm_plan* pla
     p.x = static_cast<const _Float16*>(x);
     p.packed = packed_codes;
     p.codebooks = static_cast<const _Float16*>(codebooks);
-    p.scales = static_cast<const _Float16*>(scales);
+    p.scales = g.g > 0 ? nullptr : static_cast<const _Float16*>(scales);
+    p.gscales = g.g > 0 ? static_cast<const uint8_t*>(scales) : nullptr;
+    p.GPU = g.GPU;
+    p.gshift = g.gshift;
     p.y = y;
     p.counters = static_cast<uint32_t*>(workspace);
     p.partials = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + cbytes);
@@ -67,10 +70,19 @@ extern "C" int codegemm_gemm(const codegemm_desc* desc, const codegemm_plan* pla
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (g.BG == 4) {
         switch (g.m) {
-            case 1: return launch_gemm_batch_m1(g, p, s);
-            case 2: return launch_gemm_batch_m2(g, p, s);
-            case 3: return launch_gemm_batch_m3(g, p, s);
-            case 4: return launch_gemm_batch_m4(g, p, s);
+            case 1: return g.g > 0 ? launch_gemm_batch_gs_m1(g, p, s) : launch_gemm_batch_m1(g, p, s);
+            case 2: return g.g > 0 ? launch_gemm_batch_gs_m2(g, p, s) : launch_gemm_batch_m2(g, p, s);
+            case 3: return g.g > 0 ? launch_gemm_batch_gs_m3(g, p, s) : launch_gemm_batch_m3(g, p, s);
+            case 4: return g.g > 0 ? launch_gemm_batch_gs_m4(g, p, s) : launch_gemm_batch_m4(g, p, s);
+        }
+        return CODEGEMM_UNSUPPORTED;
+    }
+    if (g.g > 0) {
+        switch (g.m) {
+            case 1: return launch_gemm_gs_m1(g, p, s);
+            case 2: return launch_gemm_gs_m2(g, p, s);
+            case 3: return launch_gemm_gs_m3(g, p, s);
+            case 4: return launch_gemm_gs_m4(g, p, s);
         }
         return CODEGEMM_UNSUPPORTED;
     }

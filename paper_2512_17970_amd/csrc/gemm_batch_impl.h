@@ -51,7 +51,7 @@ __device__ __forceinline__ float4_t psum4_at(uint32_t word, uint32_t off)
     return *reinterpret_cast<const lds_float4*>(static_cast<uintptr_t>(addr));
 }
 
-template <int M, int V, int NW, int RPL, int D>
+template <int M, int V, int NW, int RPL, int D, bool GS>
 __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
 {
     constexpr int BG = 4;                              // batch rows per pass
@@ -166,6 +166,26 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
             }
         }
     };
+    // Group scales (Section 2.2, Step 1) of tile t for this lane: per row word, the 8 fp16
+    // scales of its 8 rows for the group its slot belongs to in that tile, one 16-byte load;
+    // a ring of their own, DS tiles deep.
+    constexpr int DS = (D < 4) ? D : 4;
+    __amdgpu_buffer_rsrc_t s_rsrc[GS ? RPL : 1];
+    if constexpr (GS) {
+#pragma unroll
+        for (int q = 0; q < RPL; ++q) {
+            const int gr = blk * GPW + q * (NW / 4) + wave / 4;
+            const uint8_t* base = p.gscales + ((size_t)min(gr, p.NGR - 1) * p.NKT + kt0) * p.GPU * 256;
+            s_rsrc[q] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, gr < p.NGR ? nq * p.GPU * 256 : 0, kRsrcFlags);
+        }
+    }
+    auto load_scales = [&](half8_t (&dst)[RPL], int t) {
+        const int group = ((t % TPU) * TS + slot) >> p.gshift;       // of the tile's unit
+        const int o = ((t / TPU) * p.GPU + group) * 256 + g16 * 16;
+#pragma unroll
+        for (int q = 0; q < RPL; ++q)
+            dst[q] = __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(s_rsrc[GS ? q : 0], o, 0, 0));
+    };
     auto build = [&](float* buf, const half4_t (&xf)[XN]) {
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
@@ -186,6 +206,11 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int d = 0; d < D; ++d) load_codes(w[d], d);
+    half8_t sc[GS ? DS : 1][RPL];
+    if constexpr (GS) {
+#pragma unroll
+        for (int d = 0; d < DS; ++d) load_scales(sc[d], d);
+    }
     __builtin_amdgcn_sched_barrier(0);
 
     float acc[RPL][kRowsPerLane][BG];
@@ -233,12 +258,13 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
                         f[5] = psum4_at<1>(hi, off);
                         f[6] = psum4_at<2>(hi, off);
                         f[7] = psum4_at<3>(hi, off);
+                        const half8_t sv = sc[GS ? d % DS : 0][q];
 #pragma unroll
                         for (int r = 0; r < 8; ++r) {
-                            acc[q][r][0] += f[r].x;
-                            acc[q][r][1] += f[r].y;
-                            acc[q][r][2] += f[r].z;
-                            acc[q][r][3] += f[r].w;
+                            acc[q][r][0] = accumulate<GS>(acc[q][r][0], f[r].x, sv[r]);
+                            acc[q][r][1] = accumulate<GS>(acc[q][r][1], f[r].y, sv[r]);
+                            acc[q][r][2] = accumulate<GS>(acc[q][r][2], f[r].z, sv[r]);
+                            acc[q][r][3] = accumulate<GS>(acc[q][r][3], f[r].w, sv[r]);
                         }
                     }
                 }
@@ -249,6 +275,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
 #pragma unroll
             for (int i = 0; i < XN; ++i) xr[(d + 1) % D][i] = load_x(t + 1 + D, i);   // its ring slot is free again
             load_codes(w[d], t + D);
+            if constexpr (GS) load_scales(sc[d % DS], t + DS);
             __syncthreads();
             CG_STAMP(8 + (t < 7 ? t : 7));
         }
@@ -277,10 +304,10 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
     finish_block<NW * kWave, BG, ROWS>(p, stage, flag, tid, blk, ks, b0);
 }
 
-template <int M, int V, int NW, int RPL, int D>
+template <int M, int V, int NW, int RPL, int D, bool GS>
 int launch_gemm_batch_one(const Geometry& g, const GemmParams& p, hipStream_t stream)
 {
-    auto fn = gemm_batch_kernel<M, V, NW, RPL, D>;
+    auto fn = gemm_batch_kernel<M, V, NW, RPL, D, GS>;
     typedef PsumLayout<M> L;
     const size_t lds = (size_t)L::kBuffers * L::kBytes + 64;
     int st = set_max_lds(reinterpret_cast<const void*>(fn), lds);
@@ -290,21 +317,21 @@ int launch_gemm_batch_one(const Geometry& g, const GemmParams& p, hipStream_t st
     return hipGetLastError() == hipSuccess ? CODEGEMM_OK : CODEGEMM_LAUNCH_FAILED;
 }
 
-template <int M>
+template <int M, bool GS>
 int launch_gemm_batch_m(const Geometry& g, const GemmParams& p, hipStream_t stream)
 {
     if (g.v == 8) {
-        if (g.NW == 16 && g.RPL == 1) return launch_gemm_batch_one<M, 8, 16, 1, 4>(g, p, stream);
-        if (g.NW == 8 && g.RPL == 1) return launch_gemm_batch_one<M, 8, 8, 1, 8>(g, p, stream);
-        if (g.NW == 8 && g.RPL == 2) return launch_gemm_batch_one<M, 8, 8, 2, 8>(g, p, stream);
-        if (g.NW == 8 && g.RPL == 4) return launch_gemm_batch_one<M, 8, 8, 4, 4>(g, p, stream);
-        if (g.NW == 16 && g.RPL == 2) return launch_gemm_batch_one<M, 8, 16, 2, 2>(g, p, stream);
+        if (g.NW == 16 && g.RPL == 1) return launch_gemm_batch_one<M, 8, 16, 1, 4, GS>(g, p, stream);
+        if (g.NW == 8 && g.RPL == 1) return launch_gemm_batch_one<M, 8, 8, 1, 8, GS>(g, p, stream);
+        if (g.NW == 8 && g.RPL == 2) return launch_gemm_batch_one<M, 8, 8, 2, 8, GS>(g, p, stream);
+        if (g.NW == 8 && g.RPL == 4) return launch_gemm_batch_one<M, 8, 8, 4, 4, GS>(g, p, stream);
+        if (g.NW == 16 && g.RPL == 2) return launch_gemm_batch_one<M, 8, 16, 2, 2, GS>(g, p, stream);
     } else {
-        if (g.NW == 16 && g.RPL == 1) return launch_gemm_batch_one<M, 4, 16, 1, 4>(g, p, stream);
-        if (g.NW == 8 && g.RPL == 1) return launch_gemm_batch_one<M, 4, 8, 1, 8>(g, p, stream);
-        if (g.NW == 8 && g.RPL == 2) return launch_gemm_batch_one<M, 4, 8, 2, 8>(g, p, stream);
-        if (g.NW == 8 && g.RPL == 4) return launch_gemm_batch_one<M, 4, 8, 4, 4>(g, p, stream);
-        if (g.NW == 16 && g.RPL == 2) return launch_gemm_batch_one<M, 4, 16, 2, 2>(g, p, stream);
+        if (g.NW == 16 && g.RPL == 1) return launch_gemm_batch_one<M, 4, 16, 1, 4, GS>(g, p, stream);
+        if (g.NW == 8 && g.RPL == 1) return launch_gemm_batch_one<M, 4, 8, 1, 8, GS>(g, p, stream);
+        if (g.NW == 8 && g.RPL == 2) return launch_gemm_batch_one<M, 4, 8, 2, 8, GS>(g, p, stream);
+        if (g.NW == 8 && g.RPL == 4) return launch_gemm_batch_one<M, 4, 8, 4, 4, GS>(g, p, stream);
+        if (g.NW == 16 && g.RPL == 2) return launch_gemm_batch_one<M, 4, 16, 2, 2, GS>(g, p, stream);
     }
     return CODEGEMM_UNSUPPORTED;
 }
@@ -313,5 +340,9 @@ int launch_gemm_batch_m1(const Geometry& g, const GemmParams& p, hipStream_t str
 int launch_gemm_batch_m2(const Geometry& g, const GemmParams& p, hipStream_t stream);
 int launch_gemm_batch_m3(const Geometry& g, const GemmParams& p, hipStream_t stream);
 int launch_gemm_batch_m4(const Geometry& g, const GemmParams& p, hipStream_t stream);
+int launch_gemm_batch_gs_m1(const Geometry& g, const GemmParams& p, hipStream_t stream);   // with group scales
+int launch_gemm_batch_gs_m2(const Geometry& g, const GemmParams& p, hipStream_t stream);
+int launch_gemm_batch_gs_m3(const Geometry& g, const GemmParams& p, hipStream_t stream);
+int launch_gemm_batch_gs_m4(const Geometry& g, const GemmParams& p, hipStream_t stream);
 
 }  // namespace cg

@@ -2,5 +2,5 @@
 #include "gemm_batch_impl.h"
 
 namespace cg {
-int launch_gemm_batch_m2(const Geometry& g, const GemmParams& p, hipStream_t stream) { return launch_gemm_batch_m<2>(g, p, stream); }
+int launch_gemm_batch_m2(const Geometry& g, const GemmParams& p, hipStream_t stream) { return launch_gemm_batch_m<2, false>(g, p, stream); }
 }  // namespace cg

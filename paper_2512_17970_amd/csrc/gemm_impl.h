@@ -40,13 +40,15 @@ struct GemmParams {
     const _Float16* x;
     const uint8_t* packed;
     const _Float16* codebooks;
-    const _Float16* scales;
+    const _Float16* scales;      // [N], one per output row; nullptr when group scales are used
+    const uint8_t* gscales;      // packed group scales (see codegemm_pack_scales), or nullptr
     void* y;
     float* partials;             // [B][NKS][Npad]
     uint32_t* counters;          // [groups][row blocks]
     int B, K, N;
     int NGR, NKT, NKS, KPW, Npad;
     int y_fp32;
+    int GPU, gshift;             // scale groups per unit; a lane's group in its unit = slot >> gshift
     unsigned long long* trace;   // [grid][16] timestamps (100 MHz) when built with CODEGEMM_TRACE, else unused
 };
 
@@ -167,7 +169,8 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
         const int o = tid + i * NT;
         const int nn = n_base + o % ROWS;
         mine[i] = (o < BG * ROWS) ? stage[o] : 0.0f;
-        scale[i] = p.scales[nn < p.N ? nn : 0];                      // requested before any ticket round trip
+        // requested before any ticket round trip; with group scales the totals are already scaled
+        scale[i] = p.scales ? p.scales[nn < p.N ? nn : 0] : (_Float16)1.0f;
     }
     auto store_y = [&](int row, int nn, float val) {
         if (p.y_fp32) static_cast<float*>(p.y)[(size_t)row * p.N + nn] = val;
@@ -244,7 +247,17 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
     CG_STAMP(3);
 }
 
-template <int M, int V, int NW, int RPL, int BG, int D>
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+
+// acc + scale * psum for group scales, acc + psum otherwise.
+template <bool GS>
+__device__ __forceinline__ float accumulate(float acc, float psum, _Float16 scale)
+{
+    if constexpr (GS) return __builtin_fmaf((float)scale, psum, acc);
+    else return acc + psum;
+}
+
+template <int M, int V, int NW, int RPL, int BG, int D, bool GS>
 __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
 {
     constexpr int NTILES = 8 * M;                      // 32x32 MFMA blocks in one Psumbook
@@ -335,6 +348,26 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
             }
         }
     };
+    // Group scales (Section 2.2, Step 1) of unit u for this lane: per row word, the 8 fp16
+    // scales of its 8 rows for the group its slot belongs to, one 16-byte load.  They ride a
+    // ring of their own, two units deep.
+    constexpr int DS = 2;
+    __amdgpu_buffer_rsrc_t s_rsrc[GS ? RPL : 1];
+    int s_off = 0;
+    if constexpr (GS) {
+#pragma unroll
+        for (int q = 0; q < RPL; ++q) {
+            const int gr = granule_of(q);
+            const uint8_t* base = p.gscales + ((size_t)min(gr, p.NGR - 1) * p.NKT + kt0) * p.GPU * 256;
+            s_rsrc[q] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, gr < p.NGR ? nq * p.GPU * 256 : 0, kRsrcFlags);
+        }
+        s_off = ((lane & 31) >> p.gshift) * 256 + ((wave % 8) * 2 + khalf) * 16;
+    }
+    auto load_scales = [&](half8_t (&dst)[RPL], int u) {
+#pragma unroll
+        for (int q = 0; q < RPL; ++q)
+            dst[q] = __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(s_rsrc[GS ? q : 0], u * p.GPU * 256 + s_off, 0, 0));
+    };
     auto build = [&](float* buf, half4_t xf) {
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
@@ -354,6 +387,11 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int d = 0; d < D; ++d) load_codes(w[d], d);
+    half8_t sc[GS ? DS : 1][RPL];
+    if constexpr (GS) {
+#pragma unroll
+        for (int d = 0; d < DS; ++d) load_scales(sc[d], d);
+    }
     __builtin_amdgcn_sched_barrier(0);
 
     float acc[BG][RPL][kRowsPerLane];
@@ -402,14 +440,15 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
                             const uint32_t off = slot4 + (uint32_t)L::sub_bytes(c) +
                                                  ((uint32_t)(L::superplane(c) + par * L::kSuperplanes) << 16);
                             const uint32_t lo = w[d][q][2 * c], hi = w[d][q][2 * c + 1];
-                            acc[bb][q][0] += psum_at<0>(lo, off);
-                            acc[bb][q][1] += psum_at<1>(lo, off);
-                            acc[bb][q][2] += psum_at<2>(lo, off);
-                            acc[bb][q][3] += psum_at<3>(lo, off);
-                            acc[bb][q][4] += psum_at<0>(hi, off);
-                            acc[bb][q][5] += psum_at<1>(hi, off);
-                            acc[bb][q][6] += psum_at<2>(hi, off);
-                            acc[bb][q][7] += psum_at<3>(hi, off);
+                            const half8_t sv = sc[GS ? d % DS : 0][q];
+                            acc[bb][q][0] = accumulate<GS>(acc[bb][q][0], psum_at<0>(lo, off), sv[0]);
+                            acc[bb][q][1] = accumulate<GS>(acc[bb][q][1], psum_at<1>(lo, off), sv[1]);
+                            acc[bb][q][2] = accumulate<GS>(acc[bb][q][2], psum_at<2>(lo, off), sv[2]);
+                            acc[bb][q][3] = accumulate<GS>(acc[bb][q][3], psum_at<3>(lo, off), sv[3]);
+                            acc[bb][q][4] = accumulate<GS>(acc[bb][q][4], psum_at<0>(hi, off), sv[4]);
+                            acc[bb][q][5] = accumulate<GS>(acc[bb][q][5], psum_at<1>(hi, off), sv[5]);
+                            acc[bb][q][6] = accumulate<GS>(acc[bb][q][6], psum_at<2>(hi, off), sv[6]);
+                            acc[bb][q][7] = accumulate<GS>(acc[bb][q][7], psum_at<3>(hi, off), sv[7]);
                         }
                     }
                 }
@@ -432,6 +471,9 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
                     if (BG == 1) xr[(d + 1) % D][0] = load_x(u + 1 + D, 0);
                 }
                 if (last_bb) load_codes(w[d], u + D);                       // refill the code ring
+                if constexpr (GS) {
+                    if (last_bb) load_scales(sc[d % DS], u + DS);
+                }
                 __syncthreads();
             }
             CG_STAMP(8 + (u < 7 ? u : 7));
@@ -472,10 +514,10 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
 
 int set_max_lds(const void* fn, size_t bytes);
 
-template <int M, int V, int NW, int RPL, int BG, int D>
+template <int M, int V, int NW, int RPL, int BG, int D, bool GS>
 int launch_gemm_one(const Geometry& g, const GemmParams& p, hipStream_t stream)
 {
-    auto fn = gemm_kernel<M, V, NW, RPL, BG, D>;
+    auto fn = gemm_kernel<M, V, NW, RPL, BG, D, GS>;
     typedef PsumLayout<M> L;
     const size_t lds = (size_t)L::kBuffers * L::kBytes + 64;
     int st = set_max_lds(reinterpret_cast<const void*>(fn), lds);
@@ -487,35 +529,35 @@ int launch_gemm_one(const Geometry& g, const GemmParams& p, hipStream_t stream)
 
 // Instantiated (waves, row words per lane) pairs; the code ring holds about 64 bytes per
 // lane per codebook pair, i.e. 64-128 KB in flight per compute unit.
-template <int M, int V, int BG>
+template <int M, int V, int BG, bool GS>
 int launch_gemm_mvb(const Geometry& g, const GemmParams& p, hipStream_t stream)
 {
-    if (g.NW == 8 && g.RPL == 1) return launch_gemm_one<M, V, 8, 1, BG, 8>(g, p, stream);
-    if (g.NW == 16 && g.RPL == 1) return launch_gemm_one<M, V, 16, 1, BG, 8>(g, p, stream);
+    if (g.NW == 8 && g.RPL == 1) return launch_gemm_one<M, V, 8, 1, BG, 8, GS>(g, p, stream);
+    if (g.NW == 16 && g.RPL == 1) return launch_gemm_one<M, V, 16, 1, BG, 8, GS>(g, p, stream);
     if constexpr (BG * M <= 4) {
-        if (g.NW == 16 && g.RPL == 2) return launch_gemm_one<M, V, 16, 2, BG, 4>(g, p, stream);
+        if (g.NW == 16 && g.RPL == 2) return launch_gemm_one<M, V, 16, 2, BG, 4, GS>(g, p, stream);
     }
     if constexpr (BG * M <= 8) {   // 8 wavefronts have twice the registers per lane
-        if (g.NW == 8 && g.RPL == 2) return launch_gemm_one<M, V, 8, 2, BG, 4>(g, p, stream);
+        if (g.NW == 8 && g.RPL == 2) return launch_gemm_one<M, V, 8, 2, BG, 4, GS>(g, p, stream);
     }
-    if constexpr (BG == 1 && M <= 2) {
-        if (g.NW == 16 && g.RPL == 4) return launch_gemm_one<M, V, 16, 4, BG, 2>(g, p, stream);
+    if constexpr (BG == 1 && M <= 2 && !GS) {
+        if (g.NW == 16 && g.RPL == 4) return launch_gemm_one<M, V, 16, 4, BG, 2, GS>(g, p, stream);
     }
     return CODEGEMM_UNSUPPORTED;
 }
 
-template <int M>
+template <int M, bool GS>
 int launch_gemm_m(const Geometry& g, const GemmParams& p, hipStream_t stream)
 {
     if (g.v == 8) {
         switch (g.BG) {
-            case 1: return launch_gemm_mvb<M, 8, 1>(g, p, stream);
-            case 2: return launch_gemm_mvb<M, 8, 2>(g, p, stream);
+            case 1: return launch_gemm_mvb<M, 8, 1, GS>(g, p, stream);
+            case 2: return launch_gemm_mvb<M, 8, 2, GS>(g, p, stream);
         }
     } else {
         switch (g.BG) {
-            case 1: return launch_gemm_mvb<M, 4, 1>(g, p, stream);
-            case 2: return launch_gemm_mvb<M, 4, 2>(g, p, stream);
+            case 1: return launch_gemm_mvb<M, 4, 1, GS>(g, p, stream);
+            case 2: return launch_gemm_mvb<M, 4, 2, GS>(g, p, stream);
         }
     }
     return CODEGEMM_UNSUPPORTED;
@@ -525,5 +567,9 @@ int launch_gemm_m1(const Geometry& g, const GemmParams& p, hipStream_t stream);
 int launch_gemm_m2(const Geometry& g, const GemmParams& p, hipStream_t stream);
 int launch_gemm_m3(const Geometry& g, const GemmParams& p, hipStream_t stream);
 int launch_gemm_m4(const Geometry& g, const GemmParams& p, hipStream_t stream);
+int launch_gemm_gs_m1(const Geometry& g, const GemmParams& p, hipStream_t stream);   // with group scales
+int launch_gemm_gs_m2(const Geometry& g, const GemmParams& p, hipStream_t stream);
+int launch_gemm_gs_m3(const Geometry& g, const GemmParams& p, hipStream_t stream);
+int launch_gemm_gs_m4(const Geometry& g, const GemmParams& p, hipStream_t stream);
 
 }  // namespace cg

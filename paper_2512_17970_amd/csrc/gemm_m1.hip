@@ -2,5 +2,5 @@
 #include "gemm_impl.h"
 
 namespace cg {
-int launch_gemm_m1(const Geometry& g, const GemmParams& p, hipStream_t stream) { return launch_gemm_m<1>(g, p, stream); }
+int launch_gemm_m1(const Geometry& g, const GemmParams& p, hipStream_t stream) { return launch_gemm_m<1, false>(g, p, stream); }
 }  // namespace cg

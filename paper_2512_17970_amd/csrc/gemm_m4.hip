@@ -2,5 +2,5 @@
 #include "gemm_impl.h"
 
 namespace cg {
-int launch_gemm_m4(const Geometry& g, const GemmParams& p, hipStream_t stream) { return launch_gemm_m<4>(g, p, stream); }
+int launch_gemm_m4(const Geometry& g, const GemmParams& p, hipStream_t stream) { return launch_gemm_m<4, false>(g, p, stream); }
 }  // namespace cg

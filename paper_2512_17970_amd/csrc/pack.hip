@@ -36,6 +36,28 @@ unpack_kernel(const uint8_t* __restrict__ packed, uint8_t* __restrict__ codes,
     }
 }
 
+// One thread per packed scale: entry (granule, K tile, group of the tile, octet, row).
+__global__ void __launch_bounds__(256)
+pack_scales_kernel(const _Float16* __restrict__ scales, _Float16* __restrict__ packed,
+                   int N, int K, int v, int g, int NKT, int GPU, size_t total)
+{
+    const int groups = K / g;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (size_t)gridDim.x * blockDim.x) {
+        const int r = (int)(idx % 8);
+        const int o = (int)((idx / 8) % 16);
+        const int q = (int)((idx / 128) % GPU);
+        const int kt = (int)((idx / ((size_t)128 * GPU)) % NKT);
+        const int rg = (int)(idx / ((size_t)128 * GPU * NKT));
+        const int n = rg * kGranuleRows + o * kRowsPerLane + r;
+        const long long first_weight = ((long long)kt * kSlots) * v + (long long)q * g;   // of the group's part in this tile
+        const int grp = (int)(first_weight / g);
+        _Float16 val = (_Float16)0.0f;
+        if (n < N && first_weight < K && grp < groups) val = scales[(size_t)n * groups + grp];
+        packed[idx] = val;
+    }
+}
+
 // A plain fill kernel rather than a memset node, so the call can be captured
 // in a HIP graph.
 __global__ void __launch_bounds__(256) zero_kernel(uint32_t* p, size_t words)
@@ -79,6 +101,20 @@ extern "C" int codegemm_unpack_codes(const codegemm_desc* desc, const codegemm_p
     const size_t total = (size_t)g.m * g.N * g.J;
     hipLaunchKernelGGL(unpack_kernel, dim3(grid_for(total)), dim3(256), 0, static_cast<hipStream_t>(stream),
                        packed, codes, g.N, g.J, g.m, g.NKT);
+    return hipGetLastError() == hipSuccess ? CODEGEMM_OK : CODEGEMM_LAUNCH_FAILED;
+}
+
+extern "C" int codegemm_pack_scales(const codegemm_desc* desc, const void* scales, void* packed, void* stream)
+{
+    Geometry g;
+    int st = make_geometry(desc, nullptr, &g);
+    if (st) return st;
+    if (g.g <= 0) return CODEGEMM_INVALID_ARG;       // row-wise scales are used as they are
+    if (!scales || !packed || misaligned(scales) || misaligned(packed)) return CODEGEMM_INVALID_ARG;
+    const size_t total = (size_t)g.NGR * g.NKT * g.GPU * 128;
+    hipLaunchKernelGGL(pack_scales_kernel, dim3(grid_for(total)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const _Float16*>(scales), static_cast<_Float16*>(packed), g.N, g.K, g.v, g.g,
+                       g.NKT, g.GPU, total);
     return hipGetLastError() == hipSuccess ? CODEGEMM_OK : CODEGEMM_LAUNCH_FAILED;
 }
 

@@ -9,9 +9,17 @@ static int validate_desc(const codegemm_desc* d)
     if (d->batch < 1 || d->in_features < 1 || d->out_features < 1) return CODEGEMM_INVALID_ARG;
     if (d->vec_len != 4 && d->vec_len != 8) return CODEGEMM_UNSUPPORTED;
     if (d->num_codebooks < 1 || d->num_codebooks > 4) return CODEGEMM_UNSUPPORTED;
-    if (d->code_bits != 8 || d->group_size != -1) return CODEGEMM_UNSUPPORTED;
+    if (d->code_bits != 8) return CODEGEMM_UNSUPPORTED;
     if (d->batch > 32) return CODEGEMM_UNSUPPORTED;
     if (d->in_features % d->vec_len) return CODEGEMM_INVALID_ARG;
+    if (d->group_size != -1) {
+        // one scale per g = v * 2^i weights, groups tiling K exactly
+        const int g = d->group_size;
+        if (g < d->vec_len || g % d->vec_len) return CODEGEMM_UNSUPPORTED;
+        const int ratio = g / d->vec_len;
+        if (ratio & (ratio - 1)) return CODEGEMM_UNSUPPORTED;
+        if (d->in_features % g) return CODEGEMM_INVALID_ARG;
+    }
     if (d->flags & ~CODEGEMM_FLAG_Y_FP32) return CODEGEMM_INVALID_ARG;
     return CODEGEMM_OK;
 }
@@ -106,6 +114,14 @@ int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g
     g->NG = ceil_div(g->B, g->BG);
     g->Npad = g->NGR * kGranuleRows;
     g->y_fp32 = (d->flags & CODEGEMM_FLAG_Y_FP32) != 0;
+    g->g = d->group_size;
+    g->GPU = 0;
+    g->gshift = 0;
+    if (g->g > 0) {
+        const int ratio = g->g / g->v;                 // sub-vectors per group, a power of two
+        g->GPU = ratio >= kSlots ? 1 : kSlots / ratio;
+        while ((1 << g->gshift) < ratio && g->gshift < 5) ++g->gshift;
+    }
     return CODEGEMM_OK;
 }
 
@@ -139,6 +155,13 @@ extern "C" size_t codegemm_packed_codes_bytes(const codegemm_desc* desc, const c
     Geometry g;
     if (make_geometry(desc, plan, &g)) return 0;
     return (size_t)g.NGR * g.NKT * kGranuleRows * kSlots * g.m;
+}
+
+extern "C" size_t codegemm_packed_scales_bytes(const codegemm_desc* desc)
+{
+    Geometry g;
+    if (make_geometry(desc, nullptr, &g) || g.g <= 0) return 0;
+    return (size_t)g.NGR * g.NKT * g.GPU * 256;
 }
 
 extern "C" const char* codegemm_status_string(int status)

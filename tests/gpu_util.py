@@ -22,13 +22,17 @@ class DeviceLayer:
     def __init__(self, inp, plan=None, y_fp32=False):
         c = inp.case
         self.case = c
-        self.desc = cg.Desc.make(c.B, c.K, c.N, c.v, c.m, y_fp32=y_fp32)
+        self.desc = cg.Desc.make(c.B, c.K, c.N, c.v, c.m, y_fp32=y_fp32, g=c.g)
         self.plan = plan if plan is not None else cg.codegemm_default_plan(self.desc)
         self.y_fp32 = y_fp32
         self.x = dev(inp.x)
         self.codes = dev(inp.codes)
         self.codebooks = dev(inp.codebooks)
-        self.scales = dev(inp.scales)
+        self.scales = dev(inp.scales)                      # canonical: [N] or [N][K/g]
+        self.gemm_scales = self.scales                     # what codegemm_gemm takes
+        if c.g > 0:
+            self.gemm_scales = torch.empty(cg.codegemm_packed_scales_bytes(self.desc), dtype=torch.uint8, device="cuda")
+            cg.codegemm_pack_scales(self.desc, self.scales, self.gemm_scales, stream())
         self.packed = torch.empty(cg.codegemm_packed_codes_bytes(self.desc, self.plan), dtype=torch.uint8, device="cuda")
         cg.codegemm_pack_codes(self.desc, self.plan, self.codes, self.packed, stream())
         self.ws_bytes = cg.codegemm_workspace_bytes(self.desc, self.plan)
@@ -43,7 +47,7 @@ class DeviceLayer:
 
     def gemm(self, y=None):
         y = self.new_y() if y is None else y
-        cg.codegemm_gemm(self.desc, self.plan, self.x, self.packed, self.codebooks, self.scales, y,
+        cg.codegemm_gemm(self.desc, self.plan, self.x, self.packed, self.codebooks, self.gemm_scales, y,
                          self.ws, self.ws_bytes, stream())
         return y
 

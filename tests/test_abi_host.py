@@ -53,11 +53,26 @@ def test_default_plans_are_valid_for_all_workloads():
 def test_invalid_descriptors_are_rejected():
     for d in (cg.Desc.make(0, 512, 512, 8, 1), cg.Desc.make(1, 510, 512, 8, 1), cg.Desc.make(1, 512, 0, 8, 1),
               cg.Desc.make(1, 512, 512, 16, 1), cg.Desc.make(1, 512, 512, 8, 5), cg.Desc.make(1, 512, 512, 8, 1, b=4),
-              cg.Desc.make(1, 512, 512, 8, 1, g=128), cg.Desc.make(33, 512, 512, 8, 1)):
+              cg.Desc.make(1, 512, 512, 8, 1, g=12), cg.Desc.make(1, 512, 512, 8, 1, g=4),
+              cg.Desc.make(1, 512, 512, 8, 1, g=48), cg.Desc.make(1, 8 * 40, 512, 8, 1, g=128), cg.Desc.make(1, 512, 512, 8, 1, g=0),
+              cg.Desc.make(33, 512, 512, 8, 1)):
         assert cg.codegemm_workspace_bytes(d) == 0
         assert cg.codegemm_packed_codes_bytes(d) == 0
         with pytest.raises(cg.CodegemmError):
             cg.codegemm_default_plan(d)
+
+
+def test_packed_scales_bytes_closed_form():
+    """[NGR][NKT][groups per unit][16][8] fp16; nothing to pack for one scale per row."""
+    assert cg.codegemm_packed_scales_bytes(cg.Desc.make(1, 8192, 28672, 8, 2)) == 0
+    for (K, N, v, g) in [(8192, 28672, 8, 128), (8192, 28672, 8, 8), (4096, 1000, 4, 32), (4096, 130, 4, 1024), (1024, 1, 8, 512)]:
+        d = cg.Desc.make(1, K, N, v, 2, g=g)
+        ngr, nkt = -(-N // 128), -(-(K // v) // 32)
+        assert cg.codegemm_packed_scales_bytes(d) == ngr * nkt * max(1, 32 * v // g) * 256
+        assert cg.codegemm_workspace_bytes(d) > 0 and cg.codegemm_packed_codes_bytes(d) > 0
+    # when g covers whole units and N is a multiple of 128 the packed array is the canonical one's size
+    # times the units per group; for g <= 32 v it is exactly 2 N K / g bytes
+    assert cg.codegemm_packed_scales_bytes(cg.Desc.make(1, 8192, 28672, 8, 2, g=128)) == 2 * 28672 * 8192 // 128
 
 
 def test_invalid_plans_are_rejected():

@@ -96,6 +96,67 @@ def test_batched_kernel_long_ragged_k():
         run_case(case, plan=cg.Plan.make(waves, rw, splits, 4), dequant=False)
 
 
+# Normalisation groups along K (Section 2.2, Step 1).  K is a multiple of g; shapes have ragged
+# row blocks, several units per workgroup and groups smaller than, equal to and larger than a unit.
+GROUPED = [
+    # K, N, v, m, B, g
+    (1024, 600, 8, 2, 1, 128), (1024, 600, 8, 2, 1, 8), (1024, 130, 8, 2, 1, 16), (2048, 515, 8, 2, 1, 32),
+    (2048, 515, 8, 2, 1, 64), (1536, 300, 8, 2, 1, 256), (2048, 257, 8, 2, 1, 512), (4096, 129, 8, 2, 1, 1024),
+    (768, 1000, 4, 1, 1, 128), (512, 700, 4, 1, 1, 4), (1024, 64, 4, 1, 1, 32), (1024, 333, 4, 1, 1, 256),
+    (768, 520, 8, 1, 1, 16), (768, 520, 8, 3, 1, 128), (512, 300, 4, 4, 1, 8), (1024, 260, 8, 4, 1, 64),
+    (1024, 600, 8, 2, 2, 128), (1024, 600, 8, 2, 3, 32), (1024, 600, 8, 2, 4, 128), (2048, 515, 8, 2, 7, 8),
+    (768, 1000, 4, 1, 5, 128), (512, 700, 4, 1, 8, 4), (768, 520, 8, 3, 6, 64), (512, 300, 4, 4, 4, 16),
+    (2048, 130, 8, 1, 9, 512), (1024, 1100, 8, 2, 32, 128),
+]
+
+
+@pytest.mark.parametrize("K,N,v,m,B,g", GROUPED)
+def test_group_scales_default_plan(K, N, v, m, B, g):
+    run_case(synth.custom_case(K, N, v, m, B, seed=5150 + K + N + g, g=g))
+
+
+@pytest.mark.parametrize("waves,row_words,bg", [(8, 1, 1), (16, 1, 1), (8, 2, 1), (16, 2, 1), (8, 2, 2), (16, 1, 2),
+                                                (16, 1, 4), (8, 1, 4), (8, 2, 4), (16, 2, 4), (8, 4, 4)])
+@pytest.mark.parametrize("k_splits", [1, 3])
+@pytest.mark.parametrize("v,m,g", [(8, 2, 128), (8, 2, 8), (4, 1, 32), (8, 3, 64), (4, 4, 16), (8, 1, 512)])
+def test_group_scales_every_plan_shape(v, m, g, k_splits, waves, row_words, bg):
+    if not plan_ok(waves, row_words, m, bg):
+        pytest.skip("plan not offered for this m and batch group")
+    B = {1: 1, 2: 3, 4: 6}[bg]
+    case = synth.custom_case(max(g, v * 32) * 5, 1300, v, m, B, seed=93, g=g)
+    run_case(case, plan=cg.Plan.make(waves, row_words, k_splits, bg), dequant=False)
+
+
+def test_pack_scales_matches_documented_layout():
+    for (K, N, v, g) in [(1024, 300, 8, 128), (1024, 300, 8, 8), (2048, 129, 8, 1024), (512, 700, 4, 4), (640, 64, 4, 128)]:
+        case = synth.custom_case(K, N, v, 1, 1, seed=8, g=g)
+        inp = synth.generate(case)
+        desc = cg.Desc.make(1, K, N, v, 1, g=g)
+        say(f"[pack_scales] {case.name}")
+        nbytes = cg.codegemm_packed_scales_bytes(desc)
+        J = K // v
+        NGR, NKT = -(-N // 128), -(-J // 32)
+        GPU = max(1, 32 * v // g)
+        assert nbytes == NGR * NKT * GPU * 256
+        want = np.zeros((NGR, NKT, GPU, 16, 8), np.float16)      # the layout include/codegemm.h documents
+        for rg in range(NGR):
+            for kt in range(NKT):
+                for q in range(GPU):
+                    first = kt * 32 * v + q * g
+                    if first >= K:
+                        continue
+                    rows = np.arange(128) + 128 * rg
+                    ok = rows < N
+                    blockvals = np.zeros(128, np.float16)
+                    blockvals[ok] = inp.scales[rows[ok], first // g]
+                    want[rg, kt, q] = blockvals.reshape(16, 8)
+        packed = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        cg.codegemm_pack_scales(desc, dev(inp.scales), packed, stream())
+        torch.cuda.synchronize()
+        got = packed.cpu().numpy().view(np.float16).reshape(want.shape)
+        assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+
+
 def test_many_units_per_workgroup():
     """A long K range per workgroup: the code ring wraps many times, with a ragged last tile."""
     for (v, m, waves, rw, splits) in [(8, 2, 8, 1, 1), (8, 2, 16, 2, 2), (4, 1, 8, 2, 1), (8, 4, 16, 1, 3), (8, 3, 8, 1, 1),
@@ -192,5 +253,7 @@ def test_error_paths():
         cg.codegemm_gemm(d, None, None, t, t, t, t, t, 1 << 20)                                  # NULL
     with pytest.raises(cg.CodegemmError):
         cg.codegemm_gemm(d, cg.Plan.make(12, 1, 4), t, t, t, t, t, t, 1 << 20)                   # plan
+    for g in (12, 4, 48):                                                                        # g not v * 2^i, g < v, g not dividing K
+        assert cg.codegemm_packed_scales_bytes(cg.Desc.make(1, 512 if g != 48 else 8 * 40, 512, 8, 2, g=g)) == 0
     with pytest.raises(cg.CodegemmError):
         cg.codegemm_gemm(d, None, t[1:], t, t, t, t, t, 1 << 20)                                 # alignment
