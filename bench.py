@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c3", help="c1..c5 | a single case name from synth.workloads()")
+    ap.add_argument("--workload", default="c3", help="c1..c8 | a single case name from synth.workloads()")
     ap.add_argument("--launch", default="graph", choices=["graph", "direct"],
                     help="graph: the K timed steps are one captured HIP graph (no host launch cost); direct: plain launches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -57,7 +57,7 @@ class Layer:
         self.cg, self.torch, self.case = cg, torch, case
         inp = synth.generate(case)
         self.inp = inp
-        self.desc = cg.Desc.make(case.B, case.K, case.N, case.v, case.m)
+        self.desc = cg.Desc.make(case.B, case.K, case.N, case.v, case.m, g=case.g)
         self.plan = plan_override if plan_override is not None else cg.codegemm_default_plan(self.desc)
         dev = lambda a: torch.from_numpy(a).cuda()
         self.x, self.codes = dev(inp.x), dev(inp.codes)
@@ -70,16 +70,25 @@ class Layer:
         cg.codegemm_pack_codes(self.desc, self.plan, self.codes, self.packed[0], s)
         for r in range(1, self.R):
             self.packed[r].copy_(self.packed[0])
+        # group scales travel with the codes: one packed copy per copy of the codes
+        self.gemm_scales = [self.scales] * self.R
+        if case.g > 0:
+            sbytes = cg.codegemm_packed_scales_bytes(self.desc)
+            ps = torch.empty((self.R, sbytes), dtype=torch.uint8, device="cuda")
+            cg.codegemm_pack_scales(self.desc, self.scales, ps[0], s)
+            for r in range(1, self.R):
+                ps[r].copy_(ps[0])
+            self.gemm_scales = [ps[r] for r in range(self.R)]
         self.ws_bytes = cg.codegemm_workspace_bytes(self.desc, self.plan)
         self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device="cuda")
         cg.codegemm_workspace_init(self.ws, self.ws_bytes, s)
-        self.bytes = cg.compressed_bytes(case.B, case.K, case.N, case.v, case.m)
+        self.bytes = cg.compressed_bytes(case.B, case.K, case.N, case.v, case.m, case.g)
         self.i = 0
 
     def gemm(self, copy=None):
         r = self.i % self.R if copy is None else copy
         self.i += 1
-        self.cg.codegemm_gemm(self.desc, self.plan, self.x, self.packed[r], self.codebooks, self.scales, self.y,
+        self.cg.codegemm_gemm(self.desc, self.plan, self.x, self.packed[r], self.codebooks, self.gemm_scales[r], self.y,
                               self.ws, self.ws_bytes, self.torch.cuda.current_stream().cuda_stream)
 
     def dequant(self):
@@ -219,7 +228,7 @@ def main():
         return
     wl = synth.workloads()
     key = args.workload.lower()
-    if key in ("c1", "c2", "c3", "c4", "c5"):
+    if key in ("c1", "c2", "c3", "c4", "c5", "c6", "c7", "c8"):
         cases = wl[int(key[1])]
     else:
         cases = [synth.find_case(args.workload)]
