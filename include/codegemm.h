@@ -79,15 +79,18 @@ typedef struct codegemm_desc {
  */
 typedef struct codegemm_plan {
     int32_t waves;          /* wavefronts per workgroup: 8 or 16                                      */
-    int32_t row_words;      /* 8-row code words per lane per unit: 1, 2 or 4 (4 needs waves = 16,     */
-                            /* batch_group = 1, m <= 2; 2 needs batch_group * m <= 4, or <= 8 with    */
-                            /* waves = 8).  The workgroup                                             */
-                            /* owns 16 * waves * row_words rows                                       */
+    int32_t row_words;      /* 8-row code words per lane per unit: 1, 2 or 4.  The workgroup owns     */
+                            /* 16 * waves * row_words rows (32 * waves * row_words when batch_group   */
+                            /* = 4).  Limits (registers): batch_group 1 or 2: row_words = 2 needs     */
+                            /* batch_group * m <= 4 (<= 8 with waves = 8), row_words = 4 needs waves  */
+                            /* = 16, batch_group = 1, m <= 2 and one scale per row; batch_group 4:    */
+                            /* row_words = 4 needs waves = 8                                          */
     int32_t k_splits;       /* workgroups per row block, each taking a contiguous range of K tiles    */
                             /* (clamped to the number of K tiles).  1: every workgroup produces final */
                             /* outputs on its own.  > 1: partial sums are combined through the        */
                             /* workspace by the last workgroup to finish                               */
-    int32_t batch_group;    /* batch rows handled per pass over the codes: 1, 2 or 4                  */
+    int32_t batch_group;    /* batch rows handled per pass over the codes: 1, 2 or 4.  4 selects the  */
+                            /* batched kernel (batch axis innermost in the Psumbook, 128-bit gathers) */
     int32_t reserved[4];    /* must be zero */
 } codegemm_plan;
 

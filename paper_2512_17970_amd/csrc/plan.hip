@@ -40,7 +40,7 @@ static int validate_plan(const codegemm_desc* d, const codegemm_plan* p)
         return CODEGEMM_OK;
     }
     if (p->row_words >= 2 && p->batch_group * m > (p->waves == 8 ? 8 : 4)) return CODEGEMM_UNSUPPORTED;   // accumulators + code ring must fit in registers
-    if (p->row_words == 4 && (p->batch_group != 1 || m > 2)) return CODEGEMM_UNSUPPORTED;
+    if (p->row_words == 4 && (p->batch_group != 1 || m > 2 || d->group_size > 0)) return CODEGEMM_UNSUPPORTED;
     return CODEGEMM_OK;
 }
 
