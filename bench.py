@@ -44,6 +44,10 @@ def parse():
                     help="graph: the K timed steps are one captured HIP graph (no host launch cost); direct: plain launches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true", help="skip the per-shape cold/warm/dequant table")
+    ap.add_argument("--phases", action="store_true",
+                    help="phase table of every shape of the workload from the diagnostic build (in-kernel clock stamps)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="time every launch plan shape x K-split count for every shape of the workload (cold)")
     ap.add_argument("--psumbook", action="store_true",
                     help="instead of the GEMM: time the stand-alone Psumbook build (vector ALU and MFMA) at batch 1, 8, 32")
     ap.add_argument("--plan", default="", help="override plan for every shape: waves,row_words,k_splits[,batch_group]")
@@ -197,6 +201,58 @@ def psumbook_bench(torch, cg, synth):
                     f"{P.numel() * 4 / us * 1e-3:.0f} GB/s written, {2 * macs / us * 1e-6:.2f} TFLOP/s")
 
 
+def phases_report(torch, cg, layers):
+    """Where the time of one call goes, per shape: clock stamps of the workgroups (diagnostic build)."""
+    from paper_2512_17970_amd import phases
+    out = {}
+    for L in layers:
+        rows = phases.phase_table(torch, L.desc, L.plan, L.x, L.packed[0], L.codebooks, L.gemm_scales[0], L.y,
+                                  L.ws, L.ws_bytes)
+        out[L.case.name] = {"plan": repr(L.plan), "phases": rows}
+        log(f"{L.case.name}  {L.plan}  ({phases.workgroups(L.desc, L.plan)} workgroups per batch group; warm, one call)")
+        log(f"  {'phase':28s} {'workgroups':>10s} {'mean us':>9s} {'min us':>9s} {'max us':>9s}")
+        for r in rows:
+            log(f"  {r['phase']:28s} {r['workgroups']:10d} {r['mean_us']:9.2f} {r['min_us']:9.2f} {r['max_us']:9.2f}")
+    print(json.dumps({"phases": out}))
+
+
+def sweep_report(torch, cg, synth, cases, launch):
+    """Cold time of every offered plan shape and a range of K-split counts, per shape."""
+    out = {}
+    for case in cases:
+        d = cg.Desc.make(case.B, case.K, case.N, case.v, case.m, g=case.g)
+        default = cg.codegemm_default_plan(d)
+        bg = default.batch_group
+        ngr, nkt = -(-case.N // 128), -(-case.J // 32)
+        groups = -(-case.B // bg) if bg == 4 else 1
+        res = []
+        for waves, rw in [(8, 1), (16, 1), (8, 2), (16, 2), (16, 4), (8, 4)]:
+            gpw = rw * waves // (4 if bg == 4 else 8)
+            nblk = -(-ngr // gpw) * groups
+            cands = set()
+            for target in (128, 192, 224, 256, 384, 512):
+                ks = max(1, min(nkt, target // nblk))
+                cands.add(-(-nkt // -(-nkt // ks)))
+            for ks in sorted(cands):
+                plan = cg.Plan.make(waves, rw, ks, bg)
+                if cg.codegemm_workspace_bytes(d, plan) == 0:
+                    continue                                            # plan not offered for this format
+                L = Layer(cg, torch, synth, case, plan, copies_bytes=COLD_BYTES // 2)
+                call = graph_of(torch, L.gemm, 50).replay if launch == "graph" else (lambda L=L: [L.gemm() for _ in range(50)])
+                call(); call()
+                us = min(time_region(torch, call, 1) for _ in range(4)) * 1e3 / 50
+                res.append({"waves": waves, "row_words": rw, "k_splits": ks, "batch_group": bg,
+                            "workgroups": nblk * ks, "us_cold": us})
+                log(f"  {case.name} waves={waves} row_words={rw} k_splits={ks} workgroups={nblk * ks}: {us:.2f} us")
+                del L
+                torch.cuda.empty_cache()
+        res.sort(key=lambda r: r["us_cold"])
+        out[case.name] = {"default": repr(default), "plans": res}
+        log(f"BEST {case.name}: " + ", ".join(f"({r['waves']},{r['row_words']},{r['k_splits']}) {r['us_cold']:.2f}" for r in res[:3])
+            + f"   default {default}")
+    print(json.dumps({"sweep": out}))
+
+
 def read_traffic(key):
     """HBM bytes per launch of this workload (mean over its gemm_kernel launches) from the
     committed rocprofv3 --pmc summary, if it covers the workload."""
@@ -236,8 +292,14 @@ def main():
     if args.plan:
         plan_override = cg.Plan.make(*[int(t) for t in args.plan.split(",")])
     log(f"device: {torch.cuda.get_device_name(0)}; workload {key}: {[c.name for c in cases]}")
+    if args.sweep:
+        sweep_report(torch, cg, synth, cases, args.launch)
+        return
     layers = [Layer(cg, torch, synth, c, plan_override) for c in cases]
     torch.cuda.synchronize()
+    if args.phases:
+        phases_report(torch, cg, layers)
+        return
 
     def step():
         for L in layers:

@@ -9,6 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcodegemm.so")
+TRACE_LIB = os.path.join(PKG, "libcodegemm_trace.so")   # diagnostic build: kernels stamp their phases
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # Packed-FP32 instruction selection is switched off for every device compile.
@@ -21,15 +22,20 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = False, jobs: int = 8) -> str:
-    """Compiles every .hip file to an object (in parallel) and links the shared library."""
-    os.makedirs(os.path.join(PKG, "_build"), exist_ok=True)
+def build(verbose: bool = False, jobs: int = 8, trace: bool = False) -> str:
+    """Compiles every .hip file to an object (in parallel) and links the shared library.
+    trace=True builds the diagnostic library instead (same ABI plus codegemm_set_trace;
+    the gather kernels record clock stamps of their phases, see include/codegemm_trace.h)."""
+    out_dir = os.path.join(PKG, "_build", "trace" if trace else "main")
+    os.makedirs(out_dir, exist_ok=True)
+    extra = ["-DCODEGEMM_TRACE"] if trace else []
+    lib = TRACE_LIB if trace else LIB
     procs = []
     objs = []
     for src in sources():
-        obj = os.path.join(PKG, "_build", os.path.basename(src)[:-4] + ".o")
+        obj = os.path.join(out_dir, os.path.basename(src)[:-4] + ".o")
         objs.append(obj)
-        cmd = [HIPCC, *FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", src, "-o", obj]
+        cmd = [HIPCC, *FLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -45,10 +51,11 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
             raise RuntimeError(f"hipcc failed on {src}:\n" + "\n".join(lines))
         if verbose and lines:
             print("\n".join(lines))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build(verbose=True, trace=True))

@@ -30,8 +30,9 @@ int set_max_lds(const void* fn, size_t bytes)
 using namespace cg;
 
 #ifdef CODEGEMM_TRACE
-static unsigned long long* g_trace = nullptr;
-extern "C" void codegemm_set_trace(unsigned long long* buf) { g_trace = buf; }
+#include "codegemm_trace.h"
+static uint64_t* g_trace = nullptr;
+extern "C" void codegemm_set_trace(uint64_t* stamps) { g_trace = stamps; }
 #endif
 
 extern "C" int codegemm_gemm(const codegemm_desc* desc, const codegemm_plan* plan, const void* x,
@@ -65,7 +66,7 @@ extern "C" int codegemm_gemm(const codegemm_desc* desc, const codegemm_plan* pla
     p.y_fp32 = g.y_fp32 ? 1 : 0;
     p.trace = nullptr;
 #ifdef CODEGEMM_TRACE
-    p.trace = g_trace;
+    p.trace = reinterpret_cast<unsigned long long*>(g_trace);
 #endif
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (g.BG == 4) {

@@ -49,11 +49,11 @@ struct GemmParams {
     int NGR, NKT, NKS, KPW, Npad;
     int y_fp32;
     int GPU, gshift;             // scale groups per unit; a lane's group in its unit = slot >> gshift
-    unsigned long long* trace;   // [grid][16] timestamps (100 MHz) when built with CODEGEMM_TRACE, else unused
+    unsigned long long* trace;   // [grid][24] timestamps (100 MHz) when built with CODEGEMM_TRACE, else unused
 };
 
 #ifdef CODEGEMM_TRACE
-#define CG_STAMP(k) do { if (p.trace && threadIdx.x == 0 && blockIdx.z == 0) p.trace[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 16 + (k)] = wall_clock64(); } while (0)
+#define CG_STAMP(k) do { if (p.trace && threadIdx.x == 0 && blockIdx.z == 0) p.trace[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 24 + (k)] = wall_clock64(); } while (0)
 #else
 #define CG_STAMP(k) do { } while (0)
 #endif
@@ -156,9 +156,9 @@ template <int NT, int BG, int ROWS>
 __device__ __forceinline__ void finish_block(const GemmParams& p, const float* stage, uint32_t* flag,
                                              int tid, int blk, int ks, int b0)
 {
-    CG_STAMP(9);
+    CG_STAMP(16);
     __syncthreads();
-    CG_STAMP(10);
+    CG_STAMP(17);
 
     constexpr int PER_THREAD = (BG * ROWS + NT - 1) / NT;             // outputs per thread
     const int n_base = blk * ROWS;

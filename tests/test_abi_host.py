@@ -27,6 +27,28 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, s), s
 
 
+def test_trace_library_exports_the_abi_and_the_trace_hook():
+    """The diagnostic build exports everything codegemm.h declares plus what codegemm_trace.h declares;
+    the production library does not export the trace hook."""
+    from paper_2512_17970_amd import phases
+    text = open(os.path.join(ROOT, "include", "codegemm_trace.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    extra = sorted(set(re.findall(r"\b(codegemm_[a-z_]+)\s*\(", text)))
+    assert extra == ["codegemm_set_trace"]
+    lib = ctypes.CDLL(phases.TRACE_LIB_PATH)
+    for s in header_symbols() + extra:
+        assert hasattr(lib, s), s
+    assert not hasattr(cg.load(), "codegemm_set_trace")
+
+
+def test_phases_workgroup_count_matches_the_plan():
+    from paper_2512_17970_amd import phases
+    d = cg.Desc.make(1, 8192, 28672, 8, 2)
+    assert phases.workgroups(d, cg.Plan.make(16, 2, 4, 1)) == 224
+    assert phases.workgroups(d, cg.Plan.make(8, 1, 1000, 1)) == 224 * 32
+    assert phases.workgroups(cg.Desc.make(32, 4096, 14336, 8, 2), cg.Plan.make(16, 2, 2, 4)) == 28
+
+
 def test_status_strings():
     assert cg.codegemm_status_string(0) == "ok"
     for s in (-1, -2, -3, -4, -99):
