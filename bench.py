@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c3", help="c1..c8 | a single case name from synth.workloads()")
+    ap.add_argument("--workload", default="c3", help="c1..c10 | a single case name from synth.workloads()")
     ap.add_argument("--launch", default="graph", choices=["graph", "direct"],
                     help="graph: the K timed steps are one captured HIP graph (no host launch cost); direct: plain launches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -284,8 +284,8 @@ def main():
         return
     wl = synth.workloads()
     key = args.workload.lower()
-    if key in ("c1", "c2", "c3", "c4", "c5", "c6", "c7", "c8"):
-        cases = wl[int(key[1])]
+    if key in ("c1", "c2", "c3", "c4", "c5", "c6", "c7", "c8", "c9", "c10"):
+        cases = wl[int(key[1:])]
     else:
         cases = [synth.find_case(args.workload)]
     plan_override = None
@@ -338,6 +338,14 @@ def main():
         log("per-shape (min of 5 x 200 calls):")
         detail = per_shape_detail(torch, layers, args.launch)
         out["config"]["us_per_call_cold"] = {r["case"]: round(r["us_cold_min"], 3) for r in detail}
+        t = [r["us_cold_min"] for r in detail]
+        if key in ("c2", "c3", "c7", "c8"):
+            # the paper's Table 2 quantity: the 7 linears of a decoder block = 2 q/o + 2 k/v + gate + up + down
+            out["config"]["decoder_block_us"] = round(2 * t[0] + 2 * t[1] + 2 * t[2] + t[3], 3)
+            log(f"decoder block (2 q/o + 2 k/v + 2 gate/up + down): {out['config']['decoder_block_us']:.2f} us")
+        elif key in ("c9", "c10"):
+            out["config"]["decoder_block_us"] = round(sum(t), 3)       # fused QKV + o + fused gate-up + down
+            log(f"decoder block with fused projections (qkv + o + gate_up + down): {out['config']['decoder_block_us']:.2f} us")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cases, synth)
         log(f"cpu oracle: {out['cpu_baseline']['ms_per_step']:.1f} ms per step on {out['cpu_baseline']['cores']} threads")

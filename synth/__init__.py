@@ -62,7 +62,8 @@ def workloads() -> Dict[int, List[Case]]:
     """Workload families: 1 a tiny layer, 2 Llama-3-8B shapes (v4 m1), 3 Llama-3-70B
     shapes (v8 m2), 4 a batch sweep, 5 a bit-width sweep (all with one scale per row),
     6 a sweep of the normalisation group size g at 8192->28672, 7 and 8 the 8B and 70B
-    shapes in the formats the paper's latency table uses (m1v4g128, m2v8g128)."""
+    shapes in the formats the paper's latency table uses (m1v4g128, m2v8g128), 9 and 10 the
+    same two decoder blocks with fused projections (QKV as one matrix, gate and up as one)."""
     out: Dict[int, List[Case]] = {}
     out[1] = [_case(1, 0, 512, 512, 8, 1, 1)]
     out[2] = [_case(2, i, K, N, 4, 1, 1) for i, (K, N) in
@@ -83,6 +84,10 @@ def workloads() -> Dict[int, List[Case]]:
               enumerate([(4096, 4096), (4096, 1024), (4096, 14336), (14336, 4096)])]
     out[8] = [_case(8, i, K, N, 8, 2, 1, 128) for i, (K, N) in
               enumerate([(8192, 8192), (8192, 1024), (8192, 28672), (28672, 8192)])]
+    out[9] = [_case(9, i, K, N, 4, 1, 1, 128) for i, (K, N) in
+              enumerate([(4096, 6144), (4096, 4096), (4096, 28672), (14336, 4096)])]
+    out[10] = [_case(10, i, K, N, 8, 2, 1, 128) for i, (K, N) in
+               enumerate([(8192, 10240), (8192, 8192), (8192, 57344), (28672, 8192)])]
     return out
 
 
