@@ -62,7 +62,7 @@ typedef struct codegemm_desc {
     int32_t batch;          /* B, 1..32                                        */
     int32_t in_features;    /* K, a positive multiple of vec_len               */
     int32_t out_features;   /* N >= 1                                          */
-    int32_t vec_len;        /* v: 4 or 8                                       */
+    int32_t vec_len;        /* v: 4, 8 or 16                                   */
     int32_t num_codebooks;  /* m: 1..4                                         */
     int32_t code_bits;      /* b: must be 8 (Section 6, Limitations)           */
     int32_t group_size;     /* g: -1 (one scale per output row), or v * 2^i    */

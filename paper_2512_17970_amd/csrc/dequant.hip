@@ -147,13 +147,16 @@ extern "C" int codegemm_dequant_gemm(const codegemm_desc* desc, const void* x, c
         while ((g.v << p.gshift) < g.g) ++p.gshift;
     const size_t lds = (size_t)g.m * kCentroids * g.v * 2 + (size_t)p.nchunks * kDqChunk * g.v * 2;
     if (lds > (size_t)kMaxLds) return CODEGEMM_UNSUPPORTED;   // x does not fit in LDS (K > ~70k)
-    const void* fn = (g.v == 8) ? reinterpret_cast<const void*>(dequant_kernel<8>)
-                                : reinterpret_cast<const void*>(dequant_kernel<4>);
+    const void* fn = (g.v == 16) ? reinterpret_cast<const void*>(dequant_kernel<16>)
+                     : (g.v == 8) ? reinterpret_cast<const void*>(dequant_kernel<8>)
+                                  : reinterpret_cast<const void*>(dequant_kernel<4>);
     if ((st = set_max_lds(fn, lds)) != CODEGEMM_OK) return st;
     int gx = ceil_div(g.N, kDqWaves);
     if (gx > 2048) gx = 2048;
     const dim3 grid((unsigned)gx, (unsigned)g.B);
-    if (g.v == 8)
+    if (g.v == 16)
+        hipLaunchKernelGGL(dequant_kernel<16>, grid, dim3(kDqWaves * kWave), lds, static_cast<hipStream_t>(stream), p);
+    else if (g.v == 8)
         hipLaunchKernelGGL(dequant_kernel<8>, grid, dim3(kDqWaves * kWave), lds, static_cast<hipStream_t>(stream), p);
     else
         hipLaunchKernelGGL(dequant_kernel<4>, grid, dim3(kDqWaves * kWave), lds, static_cast<hipStream_t>(stream), p);

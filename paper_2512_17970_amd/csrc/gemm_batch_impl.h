@@ -89,7 +89,9 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
     // build roles
     const int khalf = lane >> 5;
     const bool kvalid = 4 * khalf < V;
-    const half4_t zero4 = {0, 0, 0, 0};
+    typedef typename Frag<V>::type frag_t;
+    constexpr int FE = frag_elems<V>();                // operand elements per lane
+    const frag_t zero4 = {};
 
     CG_STAMP(0);
     constexpr uint32_t kRsrcFlags = 0x00020000u;       // raw 32-bit buffer, gfx9 family
@@ -105,13 +107,13 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
     // Centroid operands of this wavefront's MFMA blocks: fixed for the whole kernel.
     // Block t: for M >= 2 codebook t / 8, centroids 32 * (t % 8)..+31, all TS = 8 slots;
     //          for M == 1 centroids 32 * (t % 8)..+31, slots 8 * (t / 8)..+7.
-    half4_t cfrag[TPW];
+    frag_t cfrag[TPW];
 #pragma unroll
     for (int i = 0; i < TPW; ++i) {
         int t = wave + i * NW;
         if (t >= NBLOCKS) t = NBLOCKS - 1;
         const int cb = (M == 1) ? 0 : t / 8;
-        cfrag[i] = *reinterpret_cast<const half4_t*>(p.codebooks + (size_t)((cb * 8 + t % 8) * 32 + (lane & 31)) * V + (kvalid ? 4 * khalf : 0));
+        cfrag[i] = *reinterpret_cast<const frag_t*>(p.codebooks + (size_t)((cb * 8 + t % 8) * 32 + (lane & 31)) * V + (kvalid ? FE * khalf : 0));
     }
     // Activation operand (Step 1): column n = lane % 32 of a block is (slot n / 4, batch row
     // n % 4); the lane supplies elements 4 * (lane / 32)..+3 of that sub-vector.  One
@@ -125,13 +127,17 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
     for (int i = 0; i < XN; ++i) {
         const int half_slots = (M == 1) ? ((wave + i * NW) / 8) * 8 : 0;
         x_j0[i] = kt0 * kSlots + half_slots + ((lane & 31) >> 2);
-        x_off0[i] = (x_row * p.K + x_j0[i] * V + 4 * khalf) * 2;
+        x_off0[i] = (x_row * p.K + x_j0[i] * V + FE * khalf) * 2;
         if (!(kvalid && x_row < p.B)) x_j0[i] = J;                    // never valid
     }
-    auto load_x = [&](int t, int i) -> half4_t {
+    auto load_x = [&](int t, int i) -> frag_t {
         const bool ok = x_j0[i] + t * TS < J;
-        const u32x2_t r = __builtin_amdgcn_raw_buffer_load_b64(x_rsrc, ok ? x_off0[i] + t * (TS * V * 2) : kOutOfRange, 0, 0);
-        return __builtin_bit_cast(half4_t, r);
+        const int off = ok ? x_off0[i] + t * (TS * V * 2) : kOutOfRange;
+        if constexpr (V == 16) {
+            return __builtin_bit_cast(frag_t, __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, off, 0, 0));
+        } else {
+            return __builtin_bit_cast(frag_t, __builtin_amdgcn_raw_buffer_load_b64(x_rsrc, off, 0, 0));
+        }
     };
     // Codes of tile t for this lane: per row word q and superplane, the 8 bytes (8 rows) of
     // its codebook at its slot.  Word q of this wavefront belongs to granule
@@ -186,18 +192,18 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
         for (int q = 0; q < RPL; ++q)
             dst[q] = __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(s_rsrc[GS ? q : 0], o, 0, 0));
     };
-    auto build = [&](float* buf, const half4_t (&xf)[XN]) {
+    auto build = [&](float* buf, const frag_t (&xf)[XN]) {
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
             const int t = wave + i * NW;
             // t / 8 selects superplane and row half: the codebook, or for M == 1 the slot half
             if (NBLOCKS % NW == 0 || t < NBLOCKS)
-                mfma_block_to_lds<(M == 1) ? 2 : M>(buf, t / 8, t % 8, lane, kvalid ? cfrag[i] : zero4, xf[(M == 1) ? i : 0]);
+                mfma_block_to_lds<(M == 1) ? 2 : M, V>(buf, t / 8, t % 8, lane, kvalid ? cfrag[i] : zero4, xf[(M == 1) ? i : 0]);
         }
     };
 
     // Prologue: activations, then codes, of the first D tiles.
-    half4_t xr[D][XN];
+    frag_t xr[D][XN];
     uint32_t w[D][RPL][SP][2];
 #pragma unroll
     for (int d = 0; d < D; ++d)
@@ -317,22 +323,23 @@ int launch_gemm_batch_one(const Geometry& g, const GemmParams& p, hipStream_t st
     return hipGetLastError() == hipSuccess ? CODEGEMM_OK : CODEGEMM_LAUNCH_FAILED;
 }
 
+template <int M, int V, bool GS>
+int launch_gemm_batch_v(const Geometry& g, const GemmParams& p, hipStream_t stream)
+{
+    if (g.NW == 16 && g.RPL == 1) return launch_gemm_batch_one<M, V, 16, 1, 4, GS>(g, p, stream);
+    if (g.NW == 8 && g.RPL == 1) return launch_gemm_batch_one<M, V, 8, 1, 8, GS>(g, p, stream);
+    if (g.NW == 8 && g.RPL == 2) return launch_gemm_batch_one<M, V, 8, 2, 8, GS>(g, p, stream);
+    if (g.NW == 8 && g.RPL == 4) return launch_gemm_batch_one<M, V, 8, 4, 4, GS>(g, p, stream);
+    if (g.NW == 16 && g.RPL == 2) return launch_gemm_batch_one<M, V, 16, 2, 2, GS>(g, p, stream);
+    return CODEGEMM_UNSUPPORTED;
+}
+
 template <int M, bool GS>
 int launch_gemm_batch_m(const Geometry& g, const GemmParams& p, hipStream_t stream)
 {
-    if (g.v == 8) {
-        if (g.NW == 16 && g.RPL == 1) return launch_gemm_batch_one<M, 8, 16, 1, 4, GS>(g, p, stream);
-        if (g.NW == 8 && g.RPL == 1) return launch_gemm_batch_one<M, 8, 8, 1, 8, GS>(g, p, stream);
-        if (g.NW == 8 && g.RPL == 2) return launch_gemm_batch_one<M, 8, 8, 2, 8, GS>(g, p, stream);
-        if (g.NW == 8 && g.RPL == 4) return launch_gemm_batch_one<M, 8, 8, 4, 4, GS>(g, p, stream);
-        if (g.NW == 16 && g.RPL == 2) return launch_gemm_batch_one<M, 8, 16, 2, 2, GS>(g, p, stream);
-    } else {
-        if (g.NW == 16 && g.RPL == 1) return launch_gemm_batch_one<M, 4, 16, 1, 4, GS>(g, p, stream);
-        if (g.NW == 8 && g.RPL == 1) return launch_gemm_batch_one<M, 4, 8, 1, 8, GS>(g, p, stream);
-        if (g.NW == 8 && g.RPL == 2) return launch_gemm_batch_one<M, 4, 8, 2, 8, GS>(g, p, stream);
-        if (g.NW == 8 && g.RPL == 4) return launch_gemm_batch_one<M, 4, 8, 4, 4, GS>(g, p, stream);
-        if (g.NW == 16 && g.RPL == 2) return launch_gemm_batch_one<M, 4, 16, 2, 2, GS>(g, p, stream);
-    }
+    if (g.v == 16) return launch_gemm_batch_v<M, 16, GS>(g, p, stream);
+    if (g.v == 8) return launch_gemm_batch_v<M, 8, GS>(g, p, stream);
+    if (g.v == 4) return launch_gemm_batch_v<M, 4, GS>(g, p, stream);
     return CODEGEMM_UNSUPPORTED;
 }
 

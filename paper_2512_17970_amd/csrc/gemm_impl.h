@@ -75,11 +75,30 @@ typedef __attribute__((address_space(3))) float lds_float;
 // the contraction is fed zeros) and receives D[8*blk + 4*(l/32) + e][l%32] in
 // accumulator 4*blk + e; for fixed (blk, e) the 32 lanes of a half-wavefront write 32
 // consecutive slots of one row.
-template <int M>
-__device__ __forceinline__ void mfma_block_to_lds(float* buf, int c, int iblk, int lane, half4_t cfrag, half4_t xfrag)
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+
+// MFMA operand of one lane: 4 fp16 values per 32x32x8 pass.  v = 4 and v = 8 take one pass
+// (for v = 4 the upper half of the contraction is fed zeros); v = 16 takes two passes, and
+// the lane holds the 8 consecutive elements 8*(l/32)..+7 of its vector: elements ..+3 feed
+// the first pass and +4..+7 the second, for both operands alike, so the two passes
+// together contract over all 16 elements.
+template <int V> struct Frag { typedef half4_t type; };
+template <> struct Frag<16> { typedef half8_t type; };
+template <int V> __host__ __device__ constexpr int frag_elems() { return V == 16 ? 8 : 4; }
+
+template <int M, int V>
+__device__ __forceinline__ void mfma_block_to_lds(float* buf, int c, int iblk, int lane,
+                                                  typename Frag<V>::type cfrag, typename Frag<V>::type xfrag)
 {
     float16_t d = {0};
-    d = __builtin_amdgcn_mfma_f32_32x32x8f16(cfrag, xfrag, d, 0, 0, 0);
+    if constexpr (V == 16) {
+        d = __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_shufflevector(cfrag, cfrag, 0, 1, 2, 3),
+                                                 __builtin_shufflevector(xfrag, xfrag, 0, 1, 2, 3), d, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_shufflevector(cfrag, cfrag, 4, 5, 6, 7),
+                                                 __builtin_shufflevector(xfrag, xfrag, 4, 5, 6, 7), d, 0, 0, 0);
+    } else {
+        d = __builtin_amdgcn_mfma_f32_32x32x8f16(cfrag, xfrag, d, 0, 0, 0);
+    }
     float* dst = buf + PsumLayout<M>::superplane(c) * 16384 + PsumLayout<M>::sub_bytes(c) / 4 +
                  (iblk * 32 + 4 * (lane >> 5)) * 64 + (lane & 31);
 #pragma unroll
@@ -247,8 +266,6 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
     CG_STAMP(3);
 }
 
-typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
-
 // acc + scale * psum for group scales, acc + psum otherwise.
 template <bool GS>
 __device__ __forceinline__ float accumulate(float acc, float psum, _Float16 scale)
@@ -282,7 +299,9 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
     const int nq = min(p.KPW, p.NKT - kt0);            // units of this workgroup (>= 1 by construction)
     const int khalf = lane >> 5;
     const bool kvalid = 4 * khalf < V;
-    const half4_t zero4 = {0, 0, 0, 0};
+    typedef typename Frag<V>::type frag_t;
+    constexpr int FE = frag_elems<V>();                // operand elements per lane
+    const frag_t zero4 = {};
 
     CG_STAMP(0);
     // All streaming loads are bounds-checked buffer loads: a load past the end of this
@@ -294,12 +313,12 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
     constexpr int kOutOfRange = 0x7ffffff0;
     //
     // Centroid operands of this wavefront's MFMA blocks: fixed for the whole kernel.
-    half4_t cfrag[TPW];
+    frag_t cfrag[TPW];
 #pragma unroll
     for (int i = 0; i < TPW; ++i) {
         int tile = wave + i * NW;                      // c*8 + iblk
         if (tile >= NTILES) tile = NTILES - 1;
-        cfrag[i] = *reinterpret_cast<const half4_t*>(p.codebooks + (size_t)(tile * 32 + (lane & 31)) * V + (kvalid ? 4 * khalf : 0));
+        cfrag[i] = *reinterpret_cast<const frag_t*>(p.codebooks + (size_t)(tile * 32 + (lane & 31)) * V + (kvalid ? FE * khalf : 0));
     }
     // Activation operand: sub-vector (32*kt + l%32), elements 4*(l/32)..+3 (Step 1), read
     // through a descriptor that covers exactly this workgroup's K range of batch row bb.
@@ -311,10 +330,15 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
         x_rsrc[bb] = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16*>(p.x + (size_t)row * p.K + (size_t)kt0 * 32 * V),
                                                        0, x_elems * 2, kRsrcFlags);
     }
-    const int x_off0 = kvalid ? ((lane & 31) * V + 4 * khalf) * 2 : kOutOfRange;
-    auto load_x = [&](int u, int bb) -> half4_t {
-        const u32x2_t t = __builtin_amdgcn_raw_buffer_load_b64(x_rsrc[bb], x_off0 + u * (32 * V * 2), 0, 0);
-        return __builtin_bit_cast(half4_t, t);
+    const int x_off0 = kvalid ? ((lane & 31) * V + FE * khalf) * 2 : kOutOfRange;
+    auto load_x = [&](int u, int bb) -> frag_t {
+        if constexpr (V == 16) {
+            const u32x4_t t = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc[bb], x_off0 + u * (32 * V * 2), 0, 0);
+            return __builtin_bit_cast(frag_t, t);
+        } else {
+            const u32x2_t t = __builtin_amdgcn_raw_buffer_load_b64(x_rsrc[bb], x_off0 + u * (32 * V * 2), 0, 0);
+            return __builtin_bit_cast(frag_t, t);
+        }
     };
     // Codes of unit u for this lane: RPL words of 8*M bytes (8 rows x M codebooks at one slot).
     // Word q (q < RPL) of this wavefront belongs to granule blk*GPW + q*(NW/8) + wave/8.
@@ -368,17 +392,17 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
         for (int q = 0; q < RPL; ++q)
             dst[q] = __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(s_rsrc[GS ? q : 0], u * p.GPU * 256 + s_off, 0, 0));
     };
-    auto build = [&](float* buf, half4_t xf) {
+    auto build = [&](float* buf, frag_t xf) {
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
             const int tile = wave + i * NW;
             if (NTILES % NW == 0 || tile < NTILES)
-                mfma_block_to_lds<M>(buf, tile / 8, tile % 8, lane, kvalid ? cfrag[i] : zero4, xf);
+                mfma_block_to_lds<M, V>(buf, tile / 8, tile % 8, lane, kvalid ? cfrag[i] : zero4, xf);
         }
     };
 
     // Prologue: activations of the first D units, then codes of the first D units.
-    half4_t xr[D][BG];
+    frag_t xr[D][BG];
     uint32_t w[D][RPL][2 * M];
 #pragma unroll
     for (int d = 0; d < D; ++d)
@@ -549,7 +573,12 @@ int launch_gemm_mvb(const Geometry& g, const GemmParams& p, hipStream_t stream)
 template <int M, bool GS>
 int launch_gemm_m(const Geometry& g, const GemmParams& p, hipStream_t stream)
 {
-    if (g.v == 8) {
+    if (g.v == 16) {
+        switch (g.BG) {
+            case 1: return launch_gemm_mvb<M, 16, 1, GS>(g, p, stream);
+            case 2: return launch_gemm_mvb<M, 16, 2, GS>(g, p, stream);
+        }
+    } else if (g.v == 8) {
         switch (g.BG) {
             case 1: return launch_gemm_mvb<M, 8, 1, GS>(g, p, stream);
             case 2: return launch_gemm_mvb<M, 8, 2, GS>(g, p, stream);

@@ -7,7 +7,7 @@ static int validate_desc(const codegemm_desc* d)
 {
     if (!d) return CODEGEMM_INVALID_ARG;
     if (d->batch < 1 || d->in_features < 1 || d->out_features < 1) return CODEGEMM_INVALID_ARG;
-    if (d->vec_len != 4 && d->vec_len != 8) return CODEGEMM_UNSUPPORTED;
+    if (d->vec_len != 4 && d->vec_len != 8 && d->vec_len != 16) return CODEGEMM_UNSUPPORTED;
     if (d->num_codebooks < 1 || d->num_codebooks > 4) return CODEGEMM_UNSUPPORTED;
     if (d->code_bits != 8) return CODEGEMM_UNSUPPORTED;
     if (d->batch > 32) return CODEGEMM_UNSUPPORTED;

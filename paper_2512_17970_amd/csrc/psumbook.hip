@@ -5,7 +5,7 @@
 //   * vector ALU: one thread per (b, j, c, i), packed fp16 dot products;
 //   * MFMA: the table is the dense product of the (B*J) x v matrix of sub-vectors
 //     with the v x 256 matrix of centroids, one 32x32x8 fp16 tile per wavefront
-//     (for v = 4 the upper half of the contraction is fed zeros).
+//     (for v = 4 the upper half of the contraction is fed zeros; v = 16 takes two passes).
 #include "cg_common.h"
 
 namespace cg {
@@ -55,18 +55,22 @@ psumbook_mfma_kernel(const _Float16* __restrict__ x, const _Float16* __restrict_
         const int iblk = (int)(t % 8);
         const int c = (int)((t / 8) % m);
         const long row0 = (t / (8 * m)) * 32;
-        half4_t a = {0, 0, 0, 0}, bm = {0, 0, 0, 0};
         const long ar = row0 + col;
-        if (4 * khalf < V) {
-            if (ar < rows) {
-                const _Float16* xv = x + ar * V + 4 * khalf;
-                a = half4_t{xv[0], xv[1], xv[2], xv[3]};
-            }
-            const _Float16* cen = codebooks + ((size_t)c * kCentroids + iblk * 32 + col) * V + 4 * khalf;
-            bm = half4_t{cen[0], cen[1], cen[2], cen[3]};
-        }
         float16_t d = {0};
-        d = __builtin_amdgcn_mfma_f32_32x32x8f16(a, bm, d, 0, 0, 0);
+#pragma unroll
+        for (int pass = 0; pass < (V + 7) / 8; ++pass) {         // 8 elements of the contraction per pass
+            half4_t a = {0, 0, 0, 0}, bm = {0, 0, 0, 0};
+            const int k0 = 8 * pass + 4 * khalf;
+            if (k0 < V) {
+                if (ar < rows) {
+                    const _Float16* xv = x + ar * V + k0;
+                    a = half4_t{xv[0], xv[1], xv[2], xv[3]};
+                }
+                const _Float16* cen = codebooks + ((size_t)c * kCentroids + iblk * 32 + col) * V + k0;
+                bm = half4_t{cen[0], cen[1], cen[2], cen[3]};
+            }
+            d = __builtin_amdgcn_mfma_f32_32x32x8f16(a, bm, d, 0, 0, 0);
+        }
 #pragma unroll
         for (int blk = 0; blk < 4; ++blk) {
 #pragma unroll
@@ -102,14 +106,18 @@ extern "C" int codegemm_psumbook_build(const codegemm_desc* desc, const void* x,
         const long tiles = ((rows + 31) / 32) * g.m * 8;
         long blocks = (tiles + 3) / 4;
         if (blocks > 16384) blocks = 16384;
-        if (g.v == 8)
+        if (g.v == 16)
+            hipLaunchKernelGGL(psumbook_mfma_kernel<16>, dim3((unsigned)blocks), dim3(256), 0, s, xh, cb, psumbook, g.m, rows, g.J);
+        else if (g.v == 8)
             hipLaunchKernelGGL(psumbook_mfma_kernel<8>, dim3((unsigned)blocks), dim3(256), 0, s, xh, cb, psumbook, g.m, rows, g.J);
         else
             hipLaunchKernelGGL(psumbook_mfma_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, s, xh, cb, psumbook, g.m, rows, g.J);
     } else {
         long blocks = rows * g.m;
         if (blocks > 65536) blocks = 65536;
-        if (g.v == 8)
+        if (g.v == 16)
+            hipLaunchKernelGGL(psumbook_valu_kernel<16>, dim3((unsigned)blocks), dim3(256), 0, s, xh, cb, psumbook, g.m, rows, g.J);
+        else if (g.v == 8)
             hipLaunchKernelGGL(psumbook_valu_kernel<8>, dim3((unsigned)blocks), dim3(256), 0, s, xh, cb, psumbook, g.m, rows, g.J);
         else
             hipLaunchKernelGGL(psumbook_valu_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, s, xh, cb, psumbook, g.m, rows, g.J);

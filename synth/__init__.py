@@ -63,7 +63,8 @@ def workloads() -> Dict[int, List[Case]]:
     shapes (v8 m2), 4 a batch sweep, 5 a bit-width sweep (all with one scale per row),
     6 a sweep of the normalisation group size g at 8192->28672, 7 and 8 the 8B and 70B
     shapes in the formats the paper's latency table uses (m1v4g128, m2v8g128), 9 and 10 the
-    same two decoder blocks with fused projections (QKV as one matrix, gate and up as one)."""
+    same two decoder blocks with fused projections (QKV as one matrix, gate and up as one),
+    11 the five formats of the paper's average-bits table (all close to 2 bits) at 8192->28672."""
     out: Dict[int, List[Case]] = {}
     out[1] = [_case(1, 0, 512, 512, 8, 1, 1)]
     out[2] = [_case(2, i, K, N, 4, 1, 1) for i, (K, N) in
@@ -88,6 +89,8 @@ def workloads() -> Dict[int, List[Case]]:
               enumerate([(4096, 6144), (4096, 4096), (4096, 28672), (14336, 4096)])]
     out[10] = [_case(10, i, K, N, 8, 2, 1, 128) for i, (K, N) in
                enumerate([(8192, 10240), (8192, 8192), (8192, 57344), (28672, 8192)])]
+    out[11] = [_case(11, i, 8192, 28672, v, m, 1, g) for i, (v, m, g) in
+               enumerate([(4, 1, -1), (8, 2, -1), (16, 4, -1), (8, 1, 16), (16, 3, 32)])]
     return out
 
 

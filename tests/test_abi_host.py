@@ -74,7 +74,7 @@ def test_default_plans_are_valid_for_all_workloads():
 
 def test_invalid_descriptors_are_rejected():
     for d in (cg.Desc.make(0, 512, 512, 8, 1), cg.Desc.make(1, 510, 512, 8, 1), cg.Desc.make(1, 512, 0, 8, 1),
-              cg.Desc.make(1, 512, 512, 16, 1), cg.Desc.make(1, 512, 512, 8, 5), cg.Desc.make(1, 512, 512, 8, 1, b=4),
+              cg.Desc.make(1, 512, 512, 32, 1), cg.Desc.make(1, 512, 512, 2, 1), cg.Desc.make(1, 512, 512, 8, 5), cg.Desc.make(1, 512, 512, 8, 1, b=4),
               cg.Desc.make(1, 512, 512, 8, 1, g=12), cg.Desc.make(1, 512, 512, 8, 1, g=4),
               cg.Desc.make(1, 512, 512, 8, 1, g=48), cg.Desc.make(1, 8 * 40, 512, 8, 1, g=128), cg.Desc.make(1, 512, 512, 8, 1, g=0),
               cg.Desc.make(33, 512, 512, 8, 1)):

@@ -41,6 +41,7 @@ SMALL = [
     (512, 512, 8, 1, 1), (512, 512, 8, 2, 1), (1032, 1000, 8, 2, 1), (520, 63, 8, 2, 1), (8, 1, 8, 1, 1),
     (4 * 131, 700, 4, 1, 1), (2048, 1537, 4, 1, 1), (776, 515, 8, 3, 1), (264, 1025, 4, 4, 1),
     (1024, 600, 8, 2, 3), (4 * 67, 130, 4, 2, 5), (1536, 2100, 8, 1, 2),
+    (16 * 70, 700, 16, 4, 1), (2048, 1030, 16, 3, 1), (16 * 33, 129, 16, 1, 1), (4096, 520, 16, 2, 2), (16 * 100, 300, 16, 4, 6),
 ]
 
 
@@ -66,7 +67,7 @@ def plan_ok(waves, row_words, m, bg=1):
 
 @pytest.mark.parametrize("waves,row_words", [(8, 1), (16, 1), (8, 2), (16, 2), (16, 4)])
 @pytest.mark.parametrize("k_splits", [1, 3, 1000])
-@pytest.mark.parametrize("v,m", [(8, 2), (4, 1), (8, 1), (4, 2), (8, 3), (4, 4), (8, 4), (4, 3)])
+@pytest.mark.parametrize("v,m", [(8, 2), (4, 1), (8, 1), (4, 2), (8, 3), (4, 4), (8, 4), (4, 3), (16, 4), (16, 3), (16, 1)])
 def test_every_plan_shape(v, m, k_splits, waves, row_words):
     if not plan_ok(waves, row_words, m):
         pytest.skip("plan not offered for this m")
@@ -79,7 +80,8 @@ def test_every_plan_shape(v, m, k_splits, waves, row_words):
                                                           (8, 1, 16, 2, 3), (8, 2, 16, 1, 3), (4, 1, 16, 1, 1), (8, 1, 8, 1, 2),
                                                           (8, 3, 8, 2, 1), (4, 3, 8, 1, 3), (8, 4, 16, 1, 2), (4, 4, 8, 2, 1),
                                                           (4, 2, 8, 2, 2), (8, 2, 16, 2, 2), (8, 2, 8, 4, 1), (4, 1, 8, 4, 2),
-                                                          (8, 3, 16, 2, 1), (4, 4, 8, 4, 3)])
+                                                          (8, 3, 16, 2, 1), (4, 4, 8, 4, 3), (16, 4, 16, 1, 2), (16, 3, 8, 2, 1),
+                                                          (16, 1, 16, 2, 2)])
 def test_batch_groups(B, bg, v, m, waves, row_words, k_splits):
     if not plan_ok(waves, row_words, m, bg):
         pytest.skip("plan not offered for this m and batch group")
@@ -107,6 +109,7 @@ GROUPED = [
     (1024, 600, 8, 2, 2, 128), (1024, 600, 8, 2, 3, 32), (1024, 600, 8, 2, 4, 128), (2048, 515, 8, 2, 7, 8),
     (768, 1000, 4, 1, 5, 128), (512, 700, 4, 1, 8, 4), (768, 520, 8, 3, 6, 64), (512, 300, 4, 4, 4, 16),
     (2048, 130, 8, 1, 9, 512), (1024, 1100, 8, 2, 32, 128),
+    (2048, 515, 16, 3, 1, 32), (2048, 300, 16, 4, 1, 16), (4096, 200, 16, 3, 5, 128), (2048, 700, 16, 2, 1, 1024),
 ]
 
 
@@ -185,7 +188,7 @@ def test_pack_matches_documented_layout_and_roundtrips():
 
 
 @pytest.mark.parametrize("use_mfma", [False, True])
-@pytest.mark.parametrize("K,v,m,B", [(512, 8, 2, 1), (4 * 67, 4, 1, 3), (8 * 45, 8, 3, 9), (1024, 4, 4, 2)])
+@pytest.mark.parametrize("K,v,m,B", [(512, 8, 2, 1), (4 * 67, 4, 1, 3), (8 * 45, 8, 3, 9), (1024, 4, 4, 2), (16 * 37, 16, 3, 2), (1024, 16, 4, 5)])
 def test_psumbook_build_eq2(K, v, m, B, use_mfma):
     case = synth.custom_case(K, 8, v, m, B, seed=5)
     say(f"[psumbook] {case.name} mfma={use_mfma}")
@@ -246,7 +249,7 @@ def test_error_paths():
     with pytest.raises(cg.CodegemmError):
         cg.codegemm_gemm(cg.Desc.make(1, 510, 512, 8, 1), None, t, t, t, t, t, t, 1 << 20)       # K % v
     with pytest.raises(cg.CodegemmError):
-        cg.codegemm_gemm(cg.Desc.make(1, 512, 512, 16, 1), None, t, t, t, t, t, t, 1 << 20)      # v
+        cg.codegemm_gemm(cg.Desc.make(1, 512, 512, 32, 1), None, t, t, t, t, t, t, 1 << 20)      # v
     with pytest.raises(cg.CodegemmError):
         cg.codegemm_gemm(d, None, t, t, t, t, t, t, 16)                                          # workspace
     with pytest.raises(cg.CodegemmError):

@@ -40,7 +40,7 @@ def brute_force(inp):
 
 # Fig. 2 illustrates a 4 x 32 matrix with v = 8; it is one of the brute-force shapes.
 @pytest.mark.parametrize("K,N,v,m,B", [(32, 4, 8, 1, 1), (16, 5, 4, 1, 2), (16, 3, 8, 2, 3),
-                                      (24, 7, 4, 3, 1), (8, 1, 8, 4, 2), (12, 6, 4, 2, 1)])
+                                      (24, 7, 4, 3, 1), (8, 1, 8, 4, 2), (12, 6, 4, 2, 1), (32, 3, 16, 3, 2), (48, 2, 16, 4, 1)])
 def test_brute_force_exact_rational(K, N, v, m, B):
     inp = tiny(K, N, v, m, B, 1000 + K + N)
     y, T = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
