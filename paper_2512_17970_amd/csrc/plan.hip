@@ -81,7 +81,10 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
     int nks = 256 / nblk;
     if (nks > nkt) nks = nkt;
     if (nks < 1) nks = 1;
-    const int kpw = ceil_div(nkt, nks);
+    int kpw = ceil_div(nkt, nks);
+    // K ranges shorter than 4 tiles cost more in the cross-workgroup reduction than the extra
+    // workgroups bring, as long as 128 workgroups remain (plan sweeps on the 8B shapes)
+    if (kpw < 4 && nblk * ceil_div(nkt, 4) >= 128) kpw = 4;
     p->k_splits = ceil_div(nkt, kpw);                     // no empty K range
 }
 
