@@ -87,10 +87,11 @@ static void dequantize_row(int n, int N, int K, int v, int m, int g,
 {
     const int J = K / v;
     for (int j = 0; j < J; ++j) {
+        /* g is a multiple of v, so the v weights of vector j share the group (v * j) / g */
+        const double scale = (g == -1) ? half_bits_to_double(scales[n])
+                                       : half_bits_to_double(scales[(size_t)n * (K / g) + (v * j) / g]);
         for (int k = 0; k < v; ++k) {
             const int kk = v * j + k;
-            const double scale = (g == -1) ? half_bits_to_double(scales[n])
-                                           : half_bits_to_double(scales[(size_t)n * (K / g) + kk / g]);
             double sum = 0.0;
             for (int c = 0; c < m; ++c) {
                 int code = codes[((size_t)c * N + n) * J + j];

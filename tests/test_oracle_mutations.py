@@ -35,10 +35,10 @@ MUTATIONS = [
      "            w[kk] = scale * sum;",
      "            w[kk] = sum;"),
     ("group scale of the next group",
-     "scales[(size_t)n * (K / g) + kk / g]",
-     "scales[(size_t)n * (K / g) + (kk / g + 1) % (K / g)]"),
+     "scales[(size_t)n * (K / g) + (v * j) / g]",
+     "scales[(size_t)n * (K / g) + ((v * j) / g + 1) % (K / g)]"),
     ("groups counted in vectors, not weights",
-     "scales[(size_t)n * (K / g) + kk / g]",
+     "scales[(size_t)n * (K / g) + (v * j) / g]",
      "scales[(size_t)n * (K / g) + (j / g) % (K / g)]"),
     ("row scale of the neighbouring row",
      "(g == -1) ? half_bits_to_double(scales[n])",
