@@ -99,12 +99,19 @@ __device__ __forceinline__ void mfma_block_to_lds(float* buf, int c, int iblk, i
     } else {
         d = __builtin_amdgcn_mfma_f32_32x32x8f16(cfrag, xfrag, d, 0, 0, 0);
     }
-    float* dst = buf + PsumLayout<M>::superplane(c) * 16384 + PsumLayout<M>::sub_bytes(c) / 4 +
-                 (iblk * 32 + 4 * (lane >> 5)) * 64 + (lane & 31);
+    // The lane's first destination as an LDS byte address the optimiser cannot see through:
+    // the 16 stores then differ only by small immediate offsets (and pair up into two-dword
+    // writes) instead of each getting an address register of its own when the buffer's
+    // constant offset does not fit an immediate.
+    uint32_t dst = (uint32_t)reinterpret_cast<uintptr_t>((lds_float*)buf) +
+                   (uint32_t)(PsumLayout<M>::superplane(c) * 65536 + PsumLayout<M>::sub_bytes(c) +
+                              ((iblk * 32 + 4 * (lane >> 5)) * 64 + (lane & 31)) * 4);
+    asm volatile("" : "+v"(dst));
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) dst[(8 * blk + e) * 64] = d[4 * blk + e];
+        for (int e = 0; e < 4; ++e)
+            *reinterpret_cast<lds_float*>(static_cast<uintptr_t>(dst + (uint32_t)(8 * blk + e) * 256u)) = d[4 * blk + e];
 }
 
 // Psum lookup: the LDS byte address gets byte 0 from the low byte of `off`
