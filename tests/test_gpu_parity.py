@@ -243,6 +243,41 @@ def test_sign_codebook_bit_exact(lo):
     assert np.array_equal(yd.cpu().numpy().astype(np.float64), y_ref)
 
 
+def test_calls_replay_correctly_from_a_hip_graph():
+    """codegemm_workspace_init and codegemm_gemm only launch kernels, so they can be captured; every
+    replay must give the eager result (the ticket counters are back at zero after each call), with
+    eager work and synchronisations between the replays."""
+    for case in (synth.custom_case(2048, 1500, 8, 2, 1, seed=61), synth.custom_case(1024, 900, 4, 1, 5, seed=62),
+                 synth.custom_case(2048, 700, 8, 2, 1, seed=63, g=128)):
+        say(f"[graph] {case.name}")
+        inp = synth.generate(case)
+        y_ref, T = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+        layer = DeviceLayer(inp)
+        y_eager = layer.gemm()
+        torch.cuda.synchronize()
+        ys = [layer.new_y() for _ in range(3)]
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                cg.codegemm_workspace_init(layer.ws, layer.ws_bytes, stream())
+                for y in ys:
+                    layer.gemm(y)
+        torch.cuda.current_stream().wait_stream(side)
+        for rep in range(3):
+            for y in ys:
+                y.fill_(float("nan"))
+            g.replay()
+            torch.cuda.synchronize()
+            for y in ys:
+                assert torch.equal(y, y_eager), f"replay {rep} differs from the eager call"
+            z = layer.gemm()                              # eager work between replays, same workspace
+            torch.cuda.synchronize()
+            assert torch.equal(z, y_eager)
+        check_against_oracle(ys[0].cpu().numpy(), y_ref, T, f"graph replay {case.name}")
+
+
 def test_error_paths():
     d = cg.Desc.make(1, 512, 512, 8, 1)
     t = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
