@@ -1,23 +1,25 @@
 // The hot path: fused Psumbook build + gather-by-code GEMV/GEMM (Section 3, Steps 1-3)
-// followed by the row scale, for gfx950.  Included by one translation unit per number
-// of codebooks (gemm_m1.hip .. gemm_m4.hip), which instantiate the kernels they need.
+// with the row scale applied at the end, or group scales (Section 2.2, Step 1) applied as
+// the partial sums are accumulated, for gfx950.  Included by one translation unit per
+// number of codebooks and scale kind (gemm_m1.hip .. gemm_m4.hip, gemm_gs_m1.hip ..
+// gemm_gs_m4.hip), which instantiate the kernels they need.
 //
 // Work decomposition.  A "unit" is 128 rows by 32 sub-vectors (32 * v weights along K);
 // its packed codes are contiguous in HBM, and so are the units of consecutive K tiles
-// of one 128-row granule.  One workgroup of NW wavefronts owns NW/8 granules and a
+// of one 128-row granule.  One workgroup of NW wavefronts owns RPL * NW/8 granules and a
 // contiguous range of K tiles (all of K when k_splits = 1) and streams through them:
-//   * a half-wavefront (32 lanes) owns 8 rows; its lane s works on slot s of every
-//     K tile, so the 32 lanes always address 32 different slots = 32 different LDS
-//     banks, whatever the code values are, and the 8 accumulators of a lane stay in
-//     registers for the whole range;
+//   * a half-wavefront (32 lanes) owns 8 rows in each of RPL granules; its lane s works
+//     on slot s of every K tile, so the 32 lanes always address 32 different slots = 32
+//     different LDS banks, whatever the code values are, and the 8 * RPL accumulators
+//     of a lane stay in registers for the whole range;
 //   * the codes of the next D units are always in flight (a register ring of 16-byte
 //     loads), so HBM streams continuously with a bounded queue;
 //   * while the lanes gather unit u from one Psumbook buffer in LDS, the matrix cores
 //     build the Psumbook of unit u+1 (Eq. 2) into the other buffer: 32x32x8 fp16 MFMA
 //     blocks whose centroid operands stay in registers for the whole kernel and whose
 //     activation operand is 8 bytes per lane per unit.  One barrier per unit;
-//   * at the end the 32 lanes of a half-wavefront are summed with cross-lane
-//     shuffles.  With k_splits = 1 that is the result: it is scaled and stored, and
+//   * at the end the 32 lanes of a half-wavefront are summed with a transposing DPP
+//     reduction.  With k_splits = 1 that is the result: it is scaled and stored, and
 //     no workgroup ever talks to another.  With k_splits > 1 each workgroup writes one
 //     fp32 partial per row to the workspace and the last one to finish a row block
 //     (atomic ticket) adds the partials in range order, scales and stores y.
