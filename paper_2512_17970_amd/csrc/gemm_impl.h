@@ -418,6 +418,10 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
 #pragma unroll
         for (int bb = 0; bb < BG; ++bb) xr[d][bb] = load_x(d, bb);
     __builtin_amdgcn_sched_barrier(0);
+    // 8-wavefront workgroups serve the short calls, where the first Psumbook is on the critical
+    // path: every wavefront's first operands go into the memory queues before anyone fills
+    // them with codes (measured: -0.1 us there, nothing for the 16-wavefront streaming calls)
+    if constexpr (NW == 8) __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int d = 0; d < D; ++d) load_codes(w[d], d);
     half8_t sc[GS ? DS : 1][RPL];
