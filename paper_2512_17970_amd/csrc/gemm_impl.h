@@ -252,7 +252,23 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
         const float* src = p.partials + (size_t)row * p.NKS * p.Npad + nn;
         float sum = 0.0f;
         int k2 = 0;
-        for (; k2 + 8 <= p.NKS; k2 += 8) {              // 8 loads in flight, added in range order
+        for (; k2 + 32 <= p.NKS; k2 += 32) {            // 32 loads in flight, added in range order
+            float v[32];
+#pragma unroll
+            for (int j = 0; j < 32; ++j)
+                v[j] = __hip_atomic_load(src + (size_t)(k2 + j) * p.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int j = 0; j < 32; ++j) sum += v[j];
+        }
+        for (; k2 + 16 <= p.NKS; k2 += 16) {
+            float v[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                v[j] = __hip_atomic_load(src + (size_t)(k2 + j) * p.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) sum += v[j];
+        }
+        for (; k2 + 8 <= p.NKS; k2 += 8) {
             float v[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j)
