@@ -327,9 +327,9 @@ def main():
         "metric": "effective HBM GB/s on compressed bytes, Llama-3-70B layer shapes, bs=1, 2-bit (us/call in config)",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 in, f32 accumulate, u8 codes", "data": "synthetic",
+        "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{key}: " + ", ".join(c.name for c in cases),
-                   "calls_per_step": len(layers), "us_per_step": ms_per_step * 1e3, "launch": args.launch,
+                   "calls_per_step": len(layers), "operands": "f16 x, codebooks, scales; u8 codes; f32 Psumbook and accumulation; f16 y", "us_per_step": ms_per_step * 1e3, "launch": args.launch,
                    "cold_copies_bytes_per_shape": COLD_BYTES},
         "roofline": roofline,
     }
