@@ -243,6 +243,30 @@ def test_sign_codebook_bit_exact(lo):
     assert np.array_equal(yd.cpu().numpy().astype(np.float64), y_ref)
 
 
+def test_random_formats_shapes_and_plans():
+    """Seeded random draws over the whole supported space: format (v, m, g), shape (ragged N and K),
+    batch, and launch plan (any plan the library accepts for the format)."""
+    rng = np.random.default_rng(20251217)
+    done = 0
+    while done < 60:
+        v = int(rng.choice([4, 8, 16]))
+        m = int(rng.integers(1, 5))
+        B = int(rng.choice([1, 1, 1, 2, 3, 4, 5, 8, 13, 32]))
+        g = int(rng.choice([-1, -1, v, 2 * v, 4 * v, 128, 256, 1024]))
+        if g != -1 and g < v:
+            g = v
+        unit = max(g, v) if g != -1 else v
+        K = unit * int(rng.integers(1, max(2, 6000 // unit)))
+        N = int(rng.integers(1, 1400))
+        bg = 1 if B == 1 else int(rng.choice([1, 2, 4]))
+        plan = cg.Plan.make(int(rng.choice([8, 16])), int(rng.choice([1, 2, 4])), int(rng.choice([1, 2, 3, 5, 64])), bg)
+        desc = cg.Desc.make(B, K, N, v, m, g=g)
+        if cg.codegemm_workspace_bytes(desc, plan) == 0:
+            continue                                  # plan not offered for this format
+        run_case(synth.custom_case(K, N, v, m, B, seed=7000 + done, g=g), plan=plan, dequant=(done % 4 == 0))
+        done += 1
+
+
 def test_calls_replay_correctly_from_a_hip_graph():
     """codegemm_workspace_init and codegemm_gemm only launch kernels, so they can be captured; every
     replay must give the eager result (the ticket counters are back at zero after each call), with
