@@ -12,7 +12,7 @@ Prints ONE JSON line: the metric is effective HBM bandwidth on compressed bytes
 the step time), with a `roofline` object for the gather kernel and a
 `cpu_baseline` object (the CPU oracle timed on this host).  Per-shape detail
 (cold and cache-warm us/call, the dequantization comparator, the ratio) goes to
-stderr and, when the directory exists, to gpurun_out/bench_detail.json.
+stderr and, with --detail-json FILE, to that file.
 """
 from __future__ import annotations
 
@@ -44,6 +44,7 @@ def parse():
                     help="graph: the K timed steps are one captured HIP graph (no host launch cost); direct: plain launches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true", help="skip the per-shape cold/warm/dequant table")
+    ap.add_argument("--detail-json", default="", help="also write the per-shape detail to this file")
     ap.add_argument("--phases", action="store_true",
                     help="phase table of every shape of the workload from the diagnostic build (in-kernel clock stamps)")
     ap.add_argument("--sweep", action="store_true",
@@ -270,7 +271,7 @@ def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only; --gpus N with N > 1 is not supported "
-              "(the path would shard by output rows without any exchange; see DESIGN.md)", file=sys.stderr)
+              "(the path would shard by output rows without any exchange)", file=sys.stderr)
         sys.exit(2)
     import torch
     import synth
@@ -351,8 +352,8 @@ def main():
         log(f"cpu oracle: {out['cpu_baseline']['ms_per_step']:.1f} ms per step on {out['cpu_baseline']['cores']} threads")
     else:
         out["cpu_baseline"] = None
-    if detail is not None and os.path.isdir(os.path.join(ROOT, "gpurun_out")):
-        with open(os.path.join(ROOT, "gpurun_out", "bench_detail.json"), "w") as f:
+    if detail is not None and args.detail_json:
+        with open(args.detail_json, "w") as f:
             json.dump({"summary": out, "per_shape": detail}, f, indent=1)
     print(json.dumps(out), flush=True)
 
