@@ -243,6 +243,33 @@ def test_sign_codebook_bit_exact(lo):
     assert np.array_equal(yd.cpu().numpy().astype(np.float64), y_ref)
 
 
+def test_diagnostic_build_gives_the_same_output_and_a_monotone_timeline():
+    """The trace library must compute exactly what the production library computes, and every
+    workgroup must pass its phases in order."""
+    from paper_2512_17970_amd import phases
+    for case, plan in ((synth.custom_case(8 * 32 * 6, 1500, 8, 2, 1, seed=71), cg.Plan.make(8, 2, 3, 1)),
+                       (synth.custom_case(8 * 32 * 4, 1100, 8, 2, 6, seed=72), cg.Plan.make(16, 1, 2, 4))):
+        say(f"[phases] {case.name} {plan}")
+        inp = synth.generate(case)
+        layer = DeviceLayer(inp, plan=plan)
+        y_prod = layer.gemm()
+        torch.cuda.synchronize()
+        y = layer.new_y()
+        rows = phases.phase_table(torch, layer.desc, layer.plan, layer.x, layer.packed, layer.codebooks, layer.gemm_scales,
+                                  y, layer.ws, layer.ws_bytes, warmup=1)
+        assert torch.equal(y, y_prod)
+        by = {r["phase"]: r for r in rows}
+        n = phases.workgroups(layer.desc, layer.plan)
+        for name in ("kernel entered", "first Psumbook built", "streaming loop done", "row totals staged", "ticket drawn"):
+            assert by[name]["workgroups"] == n, name
+        assert by["output stored"]["workgroups"] == n // min(plan.k_splits, -(-case.J // 32))
+        order = ["kernel entered", "prologue loads issued", "first Psumbook built", "streaming loop done",
+                 "row totals staged", "partial sums issued", "partial sums acknowledged", "ticket drawn"]
+        means = [by[k]["mean_us"] for k in order]
+        assert means == sorted(means), means
+        assert 0 < by["output stored"]["max_us"] < 1000
+
+
 def test_random_formats_shapes_and_plans():
     """Seeded random draws over the whole supported space: format (v, m, g), shape (ragged N and K),
     batch, and launch plan (any plan the library accepts for the format)."""
