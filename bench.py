@@ -206,11 +206,12 @@ def phases_report(torch, cg, layers):
     """Where the time of one call goes, per shape: clock stamps of the workgroups (diagnostic build)."""
     from paper_2512_17970_amd import phases
     out = {}
+    flush = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")     # 4x the memory-side cache
     for L in layers:
         rows = phases.phase_table(torch, L.desc, L.plan, L.x, L.packed[0], L.codebooks, L.gemm_scales[0], L.y,
-                                  L.ws, L.ws_bytes)
+                                  L.ws, L.ws_bytes, flush=flush)
         out[L.case.name] = {"plan": repr(L.plan), "phases": rows}
-        log(f"{L.case.name}  {L.plan}  ({phases.workgroups(L.desc, L.plan)} workgroups per batch group; warm, one call)")
+        log(f"{L.case.name}  {L.plan}  ({phases.workgroups(L.desc, L.plan)} workgroups per batch group; cold, one call)")
         log(f"  {'phase':28s} {'workgroups':>10s} {'mean us':>9s} {'min us':>9s} {'max us':>9s}")
         for r in rows:
             log(f"  {r['phase']:28s} {r['workgroups']:10d} {r['mean_us']:9.2f} {r['min_us']:9.2f} {r['max_us']:9.2f}")

@@ -202,7 +202,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
         }
     };
 
-    // Prologue: activations, then codes, of the first D tiles.
+    // Prologue: activations of the first D tiles and codes of the first; the rest of the code
+    // ring is requested after the first Psumbook has been written (as in the batch-1 kernel).
     frag_t xr[D][XN];
     uint32_t w[D][RPL][SP][2];
 #pragma unroll
@@ -210,8 +211,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
 #pragma unroll
         for (int i = 0; i < XN; ++i) xr[d][i] = load_x(d, i);
     __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int d = 0; d < D; ++d) load_codes(w[d], d);
+    load_codes(w[0], 0);
     half8_t sc[GS ? DS : 1][RPL];
     if constexpr (GS) {
 #pragma unroll
@@ -231,6 +231,9 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
 
     CG_STAMP(2);
     build(planes, xr[0]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int d = 1; d < D; ++d) load_codes(w[d], d);
 #pragma unroll
     for (int i = 0; i < XN; ++i) xr[0][i] = load_x(D, i);
     __syncthreads();

@@ -48,10 +48,13 @@ def workgroups(desc: binding.Desc, plan: binding.Plan) -> int:
 
 
 def phase_table(torch, desc, plan, x, packed_codes, codebooks, scales, y, workspace, workspace_bytes,
-                warmup: int = 3) -> List[Dict]:
+                warmup: int = 3, flush=None) -> List[Dict]:
     """Runs one traced call (after `warmup` untraced ones) on the current stream and returns,
     per phase reached, the time since the first workgroup entered the kernel: mean, min and
-    max over the workgroups that reached it, in microseconds."""
+    max over the workgroups that reached it, in microseconds.  `flush`, if given, is a device
+    tensor larger than the chip's caches that is overwritten just before the traced call, so
+    that the call reads its codes from HBM (cold); without it the warm-up calls leave them in
+    the memory-side cache."""
     lib = _trace_lib()
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -68,6 +71,8 @@ def phase_table(torch, desc, plan, x, packed_codes, codebooks, scales, y, worksp
     stamps = torch.zeros((n, SLOTS), dtype=torch.int64, device="cuda")
     lib.codegemm_set_trace(ctypes.c_void_p(stamps.data_ptr()))
     try:
+        if flush is not None:
+            flush.fill_(1)
         call()
         torch.cuda.synchronize()
     finally:
