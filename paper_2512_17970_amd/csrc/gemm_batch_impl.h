@@ -329,10 +329,10 @@ int launch_gemm_batch_one(const Geometry& g, const GemmParams& p, hipStream_t st
 template <int M, int V, bool GS>
 int launch_gemm_batch_v(const Geometry& g, const GemmParams& p, hipStream_t stream)
 {
-    if (g.NW == 16 && g.RPL == 1) return launch_gemm_batch_one<M, V, 16, 1, 4, GS>(g, p, stream);
-    if (g.NW == 8 && g.RPL == 1) return launch_gemm_batch_one<M, V, 8, 1, 8, GS>(g, p, stream);
-    if (g.NW == 8 && g.RPL == 2) return launch_gemm_batch_one<M, V, 8, 2, 8, GS>(g, p, stream);
-    if (g.NW == 8 && g.RPL == 4) return launch_gemm_batch_one<M, V, 8, 4, 4, GS>(g, p, stream);
+    if (g.NW == 16 && g.RPL == 1) return launch_gemm_batch_one<M, V, 16, 1, 2, GS>(g, p, stream);
+    if (g.NW == 8 && g.RPL == 1) return launch_gemm_batch_one<M, V, 8, 1, 2, GS>(g, p, stream);
+    if (g.NW == 8 && g.RPL == 2) return launch_gemm_batch_one<M, V, 8, 2, 2, GS>(g, p, stream);
+    if (g.NW == 8 && g.RPL == 4) return launch_gemm_batch_one<M, V, 8, 4, 2, GS>(g, p, stream);
     if (g.NW == 16 && g.RPL == 2) return launch_gemm_batch_one<M, V, 16, 2, 2, GS>(g, p, stream);
     return CODEGEMM_UNSUPPORTED;
 }

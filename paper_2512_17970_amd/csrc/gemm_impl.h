@@ -587,18 +587,22 @@ int launch_gemm_one(const Geometry& g, const GemmParams& p, hipStream_t stream)
     return hipGetLastError() == hipSuccess ? CODEGEMM_OK : CODEGEMM_LAUNCH_FAILED;
 }
 
-// Instantiated (waves, row words per lane) pairs; the code ring holds about 64 bytes per
-// lane per codebook pair, i.e. 64-128 KB in flight per compute unit.
+// Instantiated (waves, row words per lane) pairs.  The code ring is two units deep everywhere.
+// A compute unit keeps only about 32-40 KB of loads outstanding (measured: 16 wavefronts
+// issue 32 KB of 16-byte loads in 400 clocks, 64 KB in 1300 and 128 KB in 3800 warm, 8800
+// from HBM), and a wavefront that cannot issue its next load cannot build or gather either,
+// so a deeper ring only parks the wavefronts in front of the memory pipeline: with 4 units
+// the 70B calls took 0.6-2 us longer, with 6 units 50 % longer.
 template <int M, int V, int BG, bool GS>
 int launch_gemm_mvb(const Geometry& g, const GemmParams& p, hipStream_t stream)
 {
-    if (g.NW == 8 && g.RPL == 1) return launch_gemm_one<M, V, 8, 1, BG, 8, GS>(g, p, stream);
-    if (g.NW == 16 && g.RPL == 1) return launch_gemm_one<M, V, 16, 1, BG, 8, GS>(g, p, stream);
+    if (g.NW == 8 && g.RPL == 1) return launch_gemm_one<M, V, 8, 1, BG, 2, GS>(g, p, stream);
+    if (g.NW == 16 && g.RPL == 1) return launch_gemm_one<M, V, 16, 1, BG, 2, GS>(g, p, stream);
     if constexpr (BG * M <= 4) {
-        if (g.NW == 16 && g.RPL == 2) return launch_gemm_one<M, V, 16, 2, BG, 4, GS>(g, p, stream);
+        if (g.NW == 16 && g.RPL == 2) return launch_gemm_one<M, V, 16, 2, BG, 2, GS>(g, p, stream);
     }
     if constexpr (BG * M <= 8) {   // 8 wavefronts have twice the registers per lane
-        if (g.NW == 8 && g.RPL == 2) return launch_gemm_one<M, V, 8, 2, BG, 4, GS>(g, p, stream);
+        if (g.NW == 8 && g.RPL == 2) return launch_gemm_one<M, V, 8, 2, BG, 2, GS>(g, p, stream);
     }
     if constexpr (BG == 1 && M <= 2 && !GS) {
         if (g.NW == 16 && g.RPL == 4) return launch_gemm_one<M, V, 16, 4, BG, 2, GS>(g, p, stream);
