@@ -191,15 +191,22 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
     constexpr int PER_THREAD = (BG * ROWS + NT - 1) / NT;             // outputs per thread
     const int n_base = blk * ROWS;
     float mine[PER_THREAD];
-    _Float16 scale[PER_THREAD];
+    uint32_t scale_bits[PER_THREAD];
 #pragma unroll
     for (int i = 0; i < PER_THREAD; ++i) {
         const int o = tid + i * NT;
         const int nn = n_base + o % ROWS;
         mine[i] = (o < BG * ROWS) ? stage[o] : 0.0f;
         // requested before any ticket round trip; with group scales the totals are already scaled
-        scale[i] = p.scales ? p.scales[nn < p.N ? nn : 0] : (_Float16)1.0f;
+        scale_bits[i] = p.scales ? reinterpret_cast<const uint16_t*>(p.scales)[nn < p.N ? nn : 0] : 0x3c00u;
     }
+    // The scale is first touched where it is used (the pin keeps its conversion, and with it
+    // the wait for the load, from being hoisted in front of the partial-sum stores).
+    auto scale_of = [&](int i) -> float {
+        uint32_t b = scale_bits[i];
+        asm volatile("" : "+v"(b));
+        return (float)__builtin_bit_cast(_Float16, (uint16_t)b);
+    };
     auto store_y = [&](int row, int nn, float val) {
         if (p.y_fp32) static_cast<float*>(p.y)[(size_t)row * p.N + nn] = val;
         else static_cast<_Float16*>(p.y)[(size_t)row * p.N + nn] = (_Float16)val;
@@ -210,7 +217,7 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
         for (int i = 0; i < PER_THREAD; ++i) {
             const int o = tid + i * NT;
             const int row = b0 + o / ROWS, nn = n_base + o % ROWS;
-            if (o < BG * ROWS && row < p.B && nn < p.N) store_y(row, nn, mine[i] * (float)scale[i]);
+            if (o < BG * ROWS && row < p.B && nn < p.N) store_y(row, nn, mine[i] * scale_of(i));
         }
         CG_STAMP(3);
         return;
@@ -286,7 +293,7 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
         }
         for (; k2 < p.NKS; ++k2)
             sum += __hip_atomic_load(src + (size_t)k2 * p.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        store_y(row, nn, sum * (float)scale[i]);
+        store_y(row, nn, sum * scale_of(i));
     }
     CG_STAMP(3);
 }

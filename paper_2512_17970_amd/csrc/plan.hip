@@ -72,13 +72,11 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
         p->k_splits = ceil_div(nkt, ceil_div(nkt, nks4));
         return;
     }
-    // 512-row blocks for large matrices with one or two codebooks, 256-row blocks (more, shorter
+    // 512-row blocks for large matrices with up to three codebooks, 256-row blocks (more, shorter
     // K ranges; twice the registers per lane) otherwise -- from plan sweeps on the Llama-3 shapes
     const double code_positions = (double)d->out_features * J;
-    p->waves = (code_positions >= 16e6 && m <= 2 && p->batch_group * m <= 4) ? 16 : 8;
+    p->waves = (code_positions >= 16e6 && p->batch_group * m <= 4) ? 16 : 8;
     p->row_words = (p->batch_group * m <= (p->waves == 8 ? 8 : 4)) ? 2 : 1;
-    // one codebook: half the code bytes per row, so twice the rows make the same 32 KB units
-    if (p->waves == 16 && m == 1 && p->batch_group == 1 && d->group_size == -1) p->row_words = 4;
     const int nblk = ceil_div(ngr, p->row_words * p->waves / 8);
     int nks = 256 / nblk;
     if (nks > nkt) nks = nkt;
