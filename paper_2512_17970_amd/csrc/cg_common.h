@@ -13,6 +13,11 @@ constexpr int kWave = 64;           // CDNA wavefront width
 constexpr int kRowsPerLane = 8;     // output rows owned by one lane of the gather kernel
 constexpr int kSlots = 32;          // sub-vectors per K tile = lanes of a half-wavefront
 constexpr int kGranuleRows = 128;   // rows per packed unit: 16 half-wavefronts x 8 rows
+// Words between the ticket counters of two row blocks (256 bytes).  Device-scope atomics on
+// words of one cache line are served one after the other (~0.2 us each), whoever issues them:
+// with the counters of all row blocks packed into one or two lines every ticket of a launch
+// queued behind every other one (measured: 0.5-2 us per call).
+constexpr int kCounterStride = 64;
 constexpr int kMaxLds = 160 * 1024; // LDS per workgroup on gfx950
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));

@@ -130,7 +130,7 @@ int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g
 
 size_t workspace_counter_bytes(const Geometry& g)
 {
-    return ((size_t)g.NG * g.NBLK * sizeof(uint32_t) + 255) & ~(size_t)255;
+    return (size_t)g.NG * g.NBLK * kCounterStride * sizeof(uint32_t);
 }
 
 }  // namespace cg
