@@ -77,15 +77,28 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
     const double code_positions = (double)d->out_features * J;
     p->waves = (code_positions >= 16e6 && p->batch_group * m <= 4) ? 16 : 8;
     p->row_words = (p->batch_group * m <= (p->waves == 8 ? 8 : 4)) ? 2 : 1;
-    const int nblk = ceil_div(ngr, p->row_words * p->waves / 8);
-    int nks = 256 / nblk;
-    if (nks > nkt) nks = nkt;
-    if (nks < 1) nks = 1;
-    int kpw = ceil_div(nkt, nks);
-    // K ranges shorter than 4 tiles cost more in the cross-workgroup reduction than the extra
-    // workgroups bring, as long as 128 workgroups remain (plan sweeps on the 8B shapes)
-    if (kpw < 4 && nblk * ceil_div(nkt, 4) >= 128) kpw = 4;
-    p->k_splits = ceil_div(nkt, kpw);                     // no empty K range
+    // K ranges: as many as give close to, but not more than, 256 workgroups (one per compute
+    // unit).  When K is too short for that with 2 row words, blocks of half the height double
+    // the workgroups (plan sweeps: 1024-output shapes -0.3 us).
+    auto ranges = [&](int row_words, int* workgroups) {
+        const int nblk = ceil_div(ngr, row_words * p->waves / 8);
+        int nks = 256 / nblk;
+        if (nks > nkt) nks = nkt;
+        if (nks < 1) nks = 1;
+        nks = ceil_div(nkt, ceil_div(nkt, nks));          // no empty K range
+        *workgroups = nblk * nks;
+        return nks;
+    };
+    int wgs = 0;
+    p->k_splits = ranges(p->row_words, &wgs);
+    if (p->row_words == 2 && wgs <= 128) {
+        int wgs1 = 0;
+        const int nks1 = ranges(1, &wgs1);
+        if (wgs1 > wgs) {
+            p->row_words = 1;
+            p->k_splits = nks1;
+        }
+    }
 }
 
 int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g)
