@@ -65,6 +65,16 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
         const int groups = ceil_div(d->batch, 4);
         p->waves = 16;
         p->row_words = groups >= 2 ? 2 : 1;
+        if (groups == 1) {
+            // one batch group: 1024-row blocks only if every workgroup still gets 4 units of K
+            // from at most 16 K ranges
+            // (8192->28672 at batch 4: 32.4 -> 27.5 us; with 1 unit each they lose: 13.0 -> 16.6)
+            const int nblk2 = ceil_div(ngr, 8);
+            int nks2 = 256 / nblk2;
+            if (nks2 > nkt) nks2 = nkt;
+            if (nks2 < 1) nks2 = 1;
+            if (ceil_div(nkt, nks2) >= 4 && nks2 <= 16) p->row_words = 2;   // (28 ranges: 30.1 -> 32.7 us)
+        }
         const int nblk4 = ceil_div(ngr, 4 * p->row_words) * groups;
         int nks4 = 256 / nblk4;
         if (nks4 > nkt) nks4 = nkt;
