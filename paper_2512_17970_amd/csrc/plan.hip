@@ -56,7 +56,11 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
     const int J = d->in_features / d->vec_len;
     const int ngr = ceil_div(d->out_features, kGranuleRows);
     const int nkt = ceil_div(J, kSlots);
-    p->batch_group = d->batch == 1 ? 1 : (d->batch == 2 ? 2 : 4);
+    const double code_positions = (double)d->out_features * J;
+    // Two batch rows: the batch-1 kernel with the code words reused for a second Psumbook, except on
+    // large matrices, where the batched kernel wins even with two of its four batch lanes idle
+    // (8192->28672: 32.7 -> 25.6 us; 8192^2: 11.4 against 12.0)
+    p->batch_group = d->batch == 1 ? 1 : ((d->batch == 2 && code_positions < 16e6) ? 2 : 4);
     if (p->batch_group == 4) {
         // LDS- and ALU-bound.  Every workgroup rebuilds the Psumbook of its tiles, and LDS
         // writes are slow, so blocks are 1024 rows tall when there are at least two batch
@@ -84,7 +88,6 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
     }
     // 512-row blocks for large matrices with up to three codebooks, 256-row blocks (more, shorter
     // K ranges; twice the registers per lane) otherwise -- from plan sweeps on the Llama-3 shapes
-    const double code_positions = (double)d->out_features * J;
     p->waves = (code_positions >= 16e6 && p->batch_group * m <= 4) ? 16 : 8;
     p->row_words = (p->batch_group * m <= (p->waves == 8 ? 8 : 4)) ? 2 : 1;
     // K ranges: as many as give close to, but not more than, 256 workgroups (one per compute
