@@ -37,6 +37,20 @@ def test_full_size_default_plan(case):
         check_against_oracle(yd.cpu().numpy(), y_ref, T, f"codegemm_dequant_gemm {case.name}")
 
 
+@pytest.mark.parametrize("B,expect", [(2, (16, 2, 4)), (4, (16, 2, 4))])
+def test_small_batch_on_a_large_matrix_takes_the_batched_kernel(B, expect):
+    """Default plan for 2 and 4 batch rows at 8192 -> 28672: the batched kernel with 1024-row blocks."""
+    case = synth.custom_case(8192, 28672, 8, 2, B, seed=4100 + B)
+    inp = synth.generate(case)
+    y_ref, T = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+    layer = DeviceLayer(inp)
+    assert (layer.plan.waves, layer.plan.row_words, layer.plan.batch_group) == expect, layer.plan
+    y = layer.gemm()
+    torch.cuda.synchronize()
+    rel = check_against_oracle(y.cpu().numpy(), y_ref, T, f"batch {B} default plan")
+    assert rel < 6e-4
+
+
 def test_fp32_output_accuracy_at_70b_shape():
     """With fp32 output only fp32 accumulation error is left: relative L2 ~1e-6."""
     case = synth.find_case("c3_8192x28672_v8m2_b1")

@@ -75,7 +75,7 @@ def test_every_plan_shape(v, m, k_splits, waves, row_words):
     run_case(case, plan=cg.Plan.make(waves, row_words, k_splits, 1), dequant=False)
 
 
-@pytest.mark.parametrize("B,bg", [(2, 1), (2, 2), (3, 2), (3, 4), (4, 4), (5, 4), (8, 4), (8, 1), (32, 4), (7, 2)])
+@pytest.mark.parametrize("B,bg", [(2, 1), (2, 2), (2, 4), (3, 2), (3, 4), (4, 4), (5, 4), (8, 4), (8, 1), (32, 4), (7, 2)])
 @pytest.mark.parametrize("v,m,waves,row_words,k_splits", [(8, 2, 8, 1, 2), (8, 2, 16, 2, 1), (4, 1, 8, 2, 1), (8, 3, 16, 1, 2),
                                                           (8, 1, 16, 2, 3), (8, 2, 16, 1, 3), (4, 1, 16, 1, 1), (8, 1, 8, 1, 2),
                                                           (8, 3, 8, 2, 1), (4, 3, 8, 1, 3), (8, 4, 16, 1, 2), (4, 4, 8, 2, 1),
