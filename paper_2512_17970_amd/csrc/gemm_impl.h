@@ -12,8 +12,9 @@
 //     on slot s of every K tile, so the 32 lanes always address 32 different slots = 32
 //     different LDS banks, whatever the code values are, and the 8 * RPL accumulators
 //     of a lane stay in registers for the whole range;
-//   * the codes of the next D units are always in flight (a register ring of 16-byte
-//     loads), so HBM streams continuously with a bounded queue;
+//   * the codes of the next D = 2 units are requested ahead (a register ring of 16-byte
+//     loads): about what a compute unit can keep outstanding, so HBM streams continuously
+//     and no wavefront stands blocked at the issue of a load while it should gather;
 //   * while the lanes gather unit u from one Psumbook buffer in LDS, the matrix cores
 //     build the Psumbook of unit u+1 (Eq. 2) into the other buffer: 32x32x8 fp16 MFMA
 //     blocks whose centroid operands stay in registers for the whole kernel and whose
