@@ -108,8 +108,12 @@ size_t codegemm_packed_codes_bytes(const codegemm_desc *desc, const codegemm_pla
  * Prepares a workspace for codegemm_gemm: zero-fills it.  Must be enqueued once
  * after allocation, before the first codegemm_gemm that uses the workspace.
  * Every codegemm_gemm call leaves the workspace ready for the next call on the
- * same stream, so this is a one-time cost.  Two calls that use the same
- * workspace concurrently (different streams) race.
+ * same stream, so this is a one-time cost; the next call may have another
+ * shape, format or plan (the workspace starts with a 64 KB area of ticket
+ * counters that every call finds and leaves all zero, followed by fp32 partial
+ * sums that need no initial value), so one workspace of the largest
+ * codegemm_workspace_bytes() serves all layers of a model.  Two calls that use
+ * the same workspace concurrently (different streams) race.
  */
 int codegemm_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 

@@ -13,11 +13,16 @@ constexpr int kWave = 64;           // CDNA wavefront width
 constexpr int kRowsPerLane = 8;     // output rows owned by one lane of the gather kernel
 constexpr int kSlots = 32;          // sub-vectors per K tile = lanes of a half-wavefront
 constexpr int kGranuleRows = 128;   // rows per packed unit: 16 half-wavefronts x 8 rows
-// Words between the ticket counters of two row blocks (256 bytes).  Device-scope atomics on
-// words of one cache line are served one after the other (~0.2 us each), whoever issues them:
-// with the counters of all row blocks packed into one or two lines every ticket of a launch
-// queued behind every other one (measured: 0.5-2 us per call).
+// Ticket counters.  Every workspace starts with a counter area of fixed size, whatever the
+// shape and plan of the calls that use it, so that calls of different shapes can share one
+// workspace: a call leaves its counters at zero and never writes partial sums where another
+// call keeps counters.  The counters of different row blocks lie kCounterStride words (256
+// bytes) apart: device-scope atomics on words of one cache line are served one after the other
+// (~0.2 us each), whoever issues them, and with the counters packed into one or two lines every
+// ticket of a launch queued behind every other one (measured: 0.5-2 us per call).  Plans with
+// more than 256 row blocks x batch groups AND several K ranges get a smaller stride.
 constexpr int kCounterStride = 64;
+constexpr int kCounterAreaWords = 16384;   // 64 KB
 constexpr int kMaxLds = 160 * 1024; // LDS per workgroup on gfx950
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
@@ -65,7 +70,8 @@ __host__ __device__ inline size_t packed_offset(int c, int n, int j, int m, int 
 }
 
 int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g);   // status
-size_t workspace_counter_bytes(const Geometry& g);
+size_t workspace_counter_bytes(const Geometry& g);   // the fixed counter area
+int counter_stride(const Geometry& g);               // words between two row blocks' counters; 0: the plan does not fit
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 

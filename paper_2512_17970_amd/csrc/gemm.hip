@@ -60,6 +60,7 @@ extern "C" int codegemm_gemm(const codegemm_desc* desc, const codegemm_plan* pla
     p.gshift = g.gshift;
     p.y = y;
     p.counters = static_cast<uint32_t*>(workspace);
+    p.cstride = counter_stride(g);
     p.partials = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + cbytes);
     p.B = g.B; p.K = g.K; p.N = g.N;
     p.NGR = g.NGR; p.NKT = g.NKT; p.NKS = g.NKS; p.KPW = g.KPW; p.Npad = g.Npad;

@@ -47,7 +47,8 @@ struct GemmParams {
     const uint8_t* gscales;      // packed group scales (see codegemm_pack_scales), or nullptr
     void* y;
     float* partials;             // [B][NKS][Npad]
-    uint32_t* counters;          // [groups][row blocks][kCounterStride], word 0 of each is the ticket counter
+    uint32_t* counters;          // [groups][row blocks][cstride], word 0 of each is the ticket counter
+    int cstride;
     int B, K, N;
     int NGR, NKT, NKS, KPW, Npad;
     int y_fp32;
@@ -242,7 +243,7 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
     __syncthreads();
     CG_STAMP(6);
     if (tid == 0) {
-        uint32_t* ctr = p.counters + ((size_t)blockIdx.z * gridDim.y + blk) * kCounterStride;
+        uint32_t* ctr = p.counters + ((size_t)blockIdx.z * gridDim.y + blk) * p.cstride;
         const uint32_t old = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const bool last = old == (uint32_t)(p.NKS - 1);
         if (last) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call

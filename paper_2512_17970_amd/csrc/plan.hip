@@ -142,6 +142,7 @@ int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g
     g->NKS = ceil_div(g->NKT, g->KPW);          // no empty K range
     g->NG = ceil_div(g->B, g->BG);
     g->Npad = g->NGR * kGranuleRows;
+    if (counter_stride(*g) == 0) return CODEGEMM_UNSUPPORTED;   // > 16384 row blocks x batch groups with several K ranges
     g->y_fp32 = (d->flags & CODEGEMM_FLAG_Y_FP32) != 0;
     g->g = d->group_size;
     g->GPU = 0;
@@ -154,9 +155,18 @@ int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g
     return CODEGEMM_OK;
 }
 
-size_t workspace_counter_bytes(const Geometry& g)
+size_t workspace_counter_bytes(const Geometry&)
 {
-    return (size_t)g.NG * g.NBLK * kCounterStride * sizeof(uint32_t);
+    return (size_t)kCounterAreaWords * sizeof(uint32_t);
+}
+
+int counter_stride(const Geometry& g)
+{
+    if (g.NKS == 1) return kCounterStride;             // no counter is touched
+    const long long blocks = (long long)g.NG * g.NBLK;
+    int stride = kCounterStride;
+    while (stride > 1 && blocks * stride > kCounterAreaWords) stride /= 2;
+    return blocks * stride <= kCounterAreaWords ? stride : 0;
 }
 
 }  // namespace cg

@@ -72,6 +72,22 @@ def test_default_plans_are_valid_for_all_workloads():
             assert cg.codegemm_workspace_bytes(d) >= c.B * p.k_splits * ngr * 128 * 4
 
 
+def test_workspace_is_a_fixed_counter_area_plus_partial_sums():
+    """64 KB of ticket counters at a fixed place, then B x K ranges x padded rows fp32 partial sums; a plan
+    with several K ranges and more row blocks than the counter area has words is refused."""
+    for (B, K, N, v, m, plan) in [(1, 8192, 8192, 8, 2, cg.Plan.make(8, 2, 8, 1)), (1, 8192, 28672, 8, 2, cg.Plan.make(16, 2, 4, 1)),
+                                  (6, 4096, 1000, 4, 1, cg.Plan.make(16, 1, 5, 4)), (1, 512, 300, 8, 1, cg.Plan.make(8, 1, 1, 1))]:
+        d = cg.Desc.make(B, K, N, v, m)
+        nkt = -(-(K // v) // 32)
+        nks = min(plan.k_splits, nkt)
+        nks = -(-nkt // -(-nkt // nks))
+        assert cg.codegemm_workspace_bytes(d, plan) == 65536 + B * nks * (-(-N // 128) * 128) * 4
+    many_rows = cg.Desc.make(1, 512, 128 * 20000, 8, 1)               # 20000 row blocks of 128 rows
+    assert cg.codegemm_workspace_bytes(many_rows, cg.Plan.make(8, 1, 2, 1)) == 0
+    assert cg.codegemm_workspace_bytes(many_rows, cg.Plan.make(8, 1, 1, 1)) > 0
+    assert cg.codegemm_workspace_bytes(many_rows) > 0                  # the default plan does not split K there
+
+
 def test_invalid_descriptors_are_rejected():
     for d in (cg.Desc.make(0, 512, 512, 8, 1), cg.Desc.make(1, 510, 512, 8, 1), cg.Desc.make(1, 512, 0, 8, 1),
               cg.Desc.make(1, 512, 512, 32, 1), cg.Desc.make(1, 512, 512, 2, 1), cg.Desc.make(1, 512, 512, 8, 5), cg.Desc.make(1, 512, 512, 8, 1, b=4),

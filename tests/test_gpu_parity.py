@@ -294,6 +294,34 @@ def test_random_formats_shapes_and_plans():
         done += 1
 
 
+def test_one_workspace_serves_calls_of_different_shapes_and_plans():
+    """A workspace that went through codegemm_workspace_init once is shared by calls with different
+    shapes, K-range counts and kernels, interleaved and repeated: every call leaves its ticket
+    counters at zero, wherever the next call puts its own."""
+    jobs = []
+    for (K, N, v, m, B, plan) in [
+            (2048, 1300, 8, 2, 1, cg.Plan.make(8, 2, 8, 1)), (4096, 700, 8, 2, 1, cg.Plan.make(16, 2, 16, 1)),
+            (1024, 2600, 4, 1, 1, cg.Plan.make(8, 1, 3, 1)), (2048, 900, 8, 2, 6, cg.Plan.make(16, 1, 5, 4)),
+            (1536, 520, 8, 1, 2, cg.Plan.make(8, 2, 6, 2)), (2048, 1300, 8, 2, 1, None)]:
+        case = synth.custom_case(K, N, v, m, B, seed=7000 + len(jobs))
+        inp = synth.generate(case)
+        y_ref, T = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+        jobs.append((case, DeviceLayer(inp, plan=plan), y_ref, T))
+    nbytes = max(L.ws_bytes for _, L, _, _ in jobs)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    cg.codegemm_workspace_init(ws, nbytes, stream())
+    for rnd in range(3):
+        order = jobs if rnd % 2 == 0 else jobs[::-1]
+        for case, L, y_ref, T in order:
+            say(f"[shared workspace] round {rnd} {case.name} plan={L.plan}")
+            y = L.new_y()
+            cg.codegemm_gemm(L.desc, L.plan, L.x, L.packed, L.codebooks, L.gemm_scales, y, ws, nbytes, stream())
+            torch.cuda.synchronize()
+            check_against_oracle(y.cpu().numpy(), y_ref, T, f"shared workspace {case.name}")
+    # the counter area (the first 64 KB of every workspace) is all zero again
+    assert int(ws[:65536].to(torch.int64).sum().item()) == 0
+
+
 def test_calls_replay_correctly_from_a_hip_graph():
     """codegemm_workspace_init and codegemm_gemm only launch kernels, so they can be captured; every
     replay must give the eager result (the ticket counters are back at zero after each call), with
