@@ -34,11 +34,11 @@ def test_trace_library_exports_the_abi_and_the_trace_hook():
     text = open(os.path.join(ROOT, "include", "codegemm_trace.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     extra = sorted(set(re.findall(r"\b(codegemm_[a-z_]+)\s*\(", text)))
-    assert extra == ["codegemm_set_trace"]
+    assert extra == ["codegemm_probe_load_issue", "codegemm_set_trace"]
     lib = ctypes.CDLL(phases.TRACE_LIB_PATH)
     for s in header_symbols() + extra:
         assert hasattr(lib, s), s
-    assert not hasattr(cg.load(), "codegemm_set_trace")
+    assert not hasattr(cg.load(), "codegemm_set_trace") and not hasattr(cg.load(), "codegemm_probe_load_issue")
 
 
 def test_phases_workgroup_count_matches_the_plan():

@@ -270,6 +270,22 @@ def test_diagnostic_build_gives_the_same_output_and_a_monotone_timeline():
         assert 0 < by["output stored"]["max_us"] < 1000
 
 
+def test_load_issue_probe_runs_and_its_stamps_are_ordered():
+    """The probe of the diagnostic build: stamps of a wavefront are ordered (issued <= first datum <= all
+    data), and a workgroup that asks for 128 KB gets its last loads out later than one that asks for 16 KB."""
+    from paper_2512_17970_amd import phases
+    rows = phases.load_issue_probe(torch, workgroups=64, configs=((16, 1), (16, 8)), reps=2)
+    assert len(rows) == 4
+    for r in rows:
+        say(f"[probe] {r}")
+        assert 0 < r["issue_first_wave_clk"] <= r["issue_last_wave_clk"] <= r["all_data_clk"]
+        assert r["first_datum_first_wave_clk"] <= r["first_datum_last_wave_clk"] <= r["all_data_clk"]
+        assert 500 < r["shader_mhz"] < 5000
+    small = [r for r in rows if r["loads_per_lane"] == 1 and not r["cold"]][0]
+    large = [r for r in rows if r["loads_per_lane"] == 8 and not r["cold"]][0]
+    assert large["issue_last_wave_clk"] > small["issue_last_wave_clk"]
+
+
 def test_random_formats_shapes_and_plans():
     """Seeded random draws over the whole supported space: format (v, m, g), shape (ragged N and K),
     batch, and launch plan (any plan the library accepts for the format)."""
