@@ -47,8 +47,6 @@ def parse():
     ap.add_argument("--detail-json", default="", help="also write the per-shape detail to this file")
     ap.add_argument("--phases", action="store_true",
                     help="phase table of every shape of the workload from the diagnostic build (in-kernel clock stamps)")
-    ap.add_argument("--probe", action="store_true",
-                    help="instead of the GEMM: how many loads a compute unit keeps outstanding (probe kernel of the diagnostic build)")
     ap.add_argument("--sweep", action="store_true",
                     help="time every launch plan shape x K-split count for every shape of the workload (cold)")
     ap.add_argument("--psumbook", action="store_true",
@@ -204,20 +202,6 @@ def psumbook_bench(torch, cg, synth):
                     f"{P.numel() * 4 / us * 1e-3:.0f} GB/s written, {2 * macs / us * 1e-6:.2f} TFLOP/s")
 
 
-def probe_report(torch):
-    """Outstanding-load capacity of a compute unit: issue and arrival clocks of n 16-byte loads per lane."""
-    from paper_2512_17970_amd import phases
-    rows = phases.load_issue_probe(torch)
-    log("256 workgroups; clocks (shader clock) since a wavefront's own start, mean over workgroups of the first / last wavefront")
-    log(f"  {'memory':6s} {'waves':>5s} {'loads/lane':>10s} {'KB/workgroup':>12s} {'issued first':>12s} {'issued last':>11s} "
-        f"{'1st datum first':>15s} {'1st datum last':>14s} {'all data':>9s} {'MHz':>6s}")
-    for r in rows:
-        log(f"  {'HBM' if r['cold'] else 'warm':6s} {r['waves']:5d} {r['loads_per_lane']:10d} {r['bytes_per_workgroup'] // 1024:12d} "
-            f"{r['issue_first_wave_clk']:12.0f} {r['issue_last_wave_clk']:11.0f} {r['first_datum_first_wave_clk']:15.0f} "
-            f"{r['first_datum_last_wave_clk']:14.0f} {r['all_data_clk']:9.0f} {r['shader_mhz']:6.0f}")
-    print(json.dumps({"load_issue_probe": rows}))
-
-
 def phases_report(torch, cg, layers):
     """Where the time of one call goes, per shape: clock stamps of the workgroups (diagnostic build)."""
     from paper_2512_17970_amd import phases
@@ -299,9 +283,6 @@ def main():
     cg.load()
     if args.psumbook:
         psumbook_bench(torch, cg, synth)
-        return
-    if args.probe:
-        probe_report(torch)
         return
     wl = synth.workloads()
     key = args.workload.lower()

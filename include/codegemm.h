@@ -18,9 +18,11 @@
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers (HBM) unless marked "host".
  *     The descriptor and plan structs are host structs passed by pointer.
- *   - The caller owns every buffer.  The library allocates nothing, keeps no
- *     global state and never synchronises: work is enqueued on `stream`
- *     (a hipStream_t passed as void*; NULL = the default stream).
+ *   - The caller owns every buffer.  The library allocates no device memory
+ *     and never synchronises: work is enqueued on `stream` (a hipStream_t
+ *     passed as void*; NULL = the default stream).  The only state it keeps
+ *     between calls is a per-process, mutex-guarded note of which kernels have
+ *     had their LDS limit raised on which device (a one-time HIP attribute).
  *   - Inputs are read-only.  Outputs are fully overwritten.  Buffers must not
  *     alias.  Every pointer must be 16-byte aligned.
  *   - Return value: CODEGEMM_OK (0) or a negative codegemm_status.  No entry
@@ -59,9 +61,10 @@ enum {
 
 /* Problem descriptor (host struct). */
 typedef struct codegemm_desc {
-    int32_t batch;          /* B, 1..32                                        */
-    int32_t in_features;    /* K, a positive multiple of vec_len               */
-    int32_t out_features;   /* N >= 1                                          */
+    int32_t batch;          /* B, 1..65535; more than 32 rows run as several   */
+                            /* launches of up to 32 rows on the same stream    */
+    int32_t in_features;    /* K, a positive multiple of vec_len, <= 2^22      */
+    int32_t out_features;   /* N, 1..2^24                                      */
     int32_t vec_len;        /* v: 4, 8 or 16                                   */
     int32_t num_codebooks;  /* m: 1..4                                         */
     int32_t code_bits;      /* b: must be 8 (Section 6, Limitations)           */
@@ -143,6 +146,14 @@ int codegemm_pack_codes(const codegemm_desc *desc, const codegemm_plan *plan,
                         const uint8_t *codes, uint8_t *packed, void *stream);
 int codegemm_unpack_codes(const codegemm_desc *desc, const codegemm_plan *plan,
                           const uint8_t *packed, uint8_t *codes, void *stream);
+
+/*
+ * The same two re-orderings on the host: `codes` and `packed` are HOST pointers,
+ * the call is synchronous and touches no GPU (for packing a checkpoint where it
+ * is loaded).  Byte for byte the result of the device calls.
+ */
+int codegemm_pack_codes_host(const codegemm_desc *desc, const uint8_t *codes, uint8_t *packed);
+int codegemm_unpack_codes_host(const codegemm_desc *desc, const uint8_t *packed, uint8_t *codes);
 
 /*
  * Scales of a layer with group_size = g > 0 (Section 2.2, Step 1), re-ordered

@@ -32,22 +32,6 @@ extern "C" {
  */
 void codegemm_set_trace(uint64_t *stamps);
 
-/*
- * Probe of how many vector loads a compute unit keeps outstanding (the fact the
- * depth of the gather kernels' code ring is chosen by).  Launches `workgroups`
- * workgroups of `waves` (1..16) wavefronts; every lane issues `loads_per_lane`
- * (1, 2, 4 or 8) coalesced 16-byte loads from its workgroup's own stretch of
- * `src` (device, 16-byte aligned, src_bytes >= workgroups * waves * 64 * 16 *
- * loads_per_lane + 16; read only) and then waits for them.  `out` (device,
- * caller-owned): uint64 [workgroups][waves][4] followed by 8 spare bytes; per
- * wavefront, shader-clock counts since its own start at which [0] its loads
- * were all issued, [1] its first datum was there, [2] all its data were there,
- * and [3] that last span in ticks of the constant 100 MHz clock.  Returns a
- * CODEGEMM_* status; enqueues on `stream`, does not synchronise.
- */
-int codegemm_probe_load_issue(const void *src, size_t src_bytes, int workgroups, int waves,
-                              int loads_per_lane, uint64_t *out, void *stream);
-
 #ifdef __cplusplus
 }
 #endif

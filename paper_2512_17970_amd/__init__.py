@@ -11,4 +11,5 @@ from .binding import (  # noqa: F401
     compressed_bytes,
     codegemm_packed_scales_bytes,
     codegemm_pack_scales,
+    codegemm_pack_codes_host, codegemm_unpack_codes_host,
 )

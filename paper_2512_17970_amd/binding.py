@@ -21,6 +21,7 @@ FLAG_Y_FP32 = 1
 EXPORTS = [
     "codegemm_default_plan", "codegemm_workspace_bytes", "codegemm_packed_codes_bytes",
     "codegemm_workspace_init", "codegemm_pack_codes", "codegemm_unpack_codes",
+    "codegemm_pack_codes_host", "codegemm_unpack_codes_host",
     "codegemm_packed_scales_bytes", "codegemm_pack_scales",
     "codegemm_psumbook_build", "codegemm_gemm", "codegemm_dequant_gemm", "codegemm_status_string",
 ]
@@ -84,6 +85,10 @@ def load() -> ctypes.CDLL:
     lib.codegemm_pack_codes.restype = i
     lib.codegemm_unpack_codes.argtypes = [dp, pp, vp, vp, vp]
     lib.codegemm_unpack_codes.restype = i
+    lib.codegemm_pack_codes_host.argtypes = [dp, vp, vp]
+    lib.codegemm_pack_codes_host.restype = i
+    lib.codegemm_unpack_codes_host.argtypes = [dp, vp, vp]
+    lib.codegemm_unpack_codes_host.restype = i
     lib.codegemm_packed_scales_bytes.argtypes = [dp]
     lib.codegemm_packed_scales_bytes.restype = sz
     lib.codegemm_pack_scales.argtypes = [dp, vp, vp, vp]
@@ -148,6 +153,24 @@ def codegemm_pack_codes(desc: Desc, plan: Optional[Plan], codes, packed, stream:
 def codegemm_unpack_codes(desc: Desc, plan: Optional[Plan], packed, codes, stream: int = 0) -> None:
     _check(load().codegemm_unpack_codes(ctypes.byref(desc), _plan(plan), _ptr(packed), _ptr(codes),
                                         ctypes.c_void_p(stream)), "codegemm_unpack_codes")
+
+
+def _host_ptr(a) -> ctypes.c_void_p:
+    """Address of a C-contiguous uint8 numpy array (host memory)."""
+    if not (a.flags["C_CONTIGUOUS"] and a.dtype.itemsize == 1):
+        raise TypeError("expected a C-contiguous uint8 array")
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def codegemm_pack_codes_host(desc: Desc, codes, packed) -> None:
+    """codes, packed: numpy uint8 arrays in host memory."""
+    _check(load().codegemm_pack_codes_host(ctypes.byref(desc), _host_ptr(codes), _host_ptr(packed)),
+           "codegemm_pack_codes_host")
+
+
+def codegemm_unpack_codes_host(desc: Desc, packed, codes) -> None:
+    _check(load().codegemm_unpack_codes_host(ctypes.byref(desc), _host_ptr(packed), _host_ptr(codes)),
+           "codegemm_unpack_codes_host")
 
 
 def codegemm_packed_scales_bytes(desc: Desc) -> int:

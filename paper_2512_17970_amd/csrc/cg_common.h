@@ -24,6 +24,11 @@ constexpr int kGranuleRows = 128;   // rows per packed unit: 16 half-wavefronts 
 constexpr int kCounterStride = 64;
 constexpr int kCounterAreaWords = 16384;   // 64 KB
 constexpr int kMaxLds = 160 * 1024; // LDS per workgroup on gfx950
+constexpr int kBatchPerLaunch = 32;         // batch rows one launch of a gather kernel takes; more rows = more launches
+constexpr int kMaxBatch = 65535;            // grid limit of the comparator (one grid row per batch row)
+constexpr int kMaxInFeatures = 1 << 22;     // K: a workgroup's code range (K/v/32 units of 4096 m bytes) and a row of
+                                            // x stay below 2^31 bytes, which the 32-bit buffer offsets require
+constexpr int kMaxOutFeatures = 1 << 24;    // N: row indices and padded row counts stay in 32-bit ints
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));

@@ -153,7 +153,7 @@ extern "C" int codegemm_dequant_gemm(const codegemm_desc* desc, const void* x, c
     if ((st = set_max_lds(fn, lds)) != CODEGEMM_OK) return st;
     int gx = ceil_div(g.N, kDqWaves);
     if (gx > 2048) gx = 2048;
-    const dim3 grid((unsigned)gx, (unsigned)g.B);
+    const dim3 grid((unsigned)gx, (unsigned)desc->batch);
     if (g.v == 16)
         hipLaunchKernelGGL(dequant_kernel<16>, grid, dim3(kDqWaves * kWave), lds, static_cast<hipStream_t>(stream), p);
     else if (g.v == 8)

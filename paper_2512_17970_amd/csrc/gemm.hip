@@ -19,6 +19,11 @@ int set_max_lds(const void* fn, size_t bytes)
     std::lock_guard<std::mutex> lock(mu);
     for (const auto& e : done)
         if (e.first == fn && e.second == dev) return CODEGEMM_OK;
+    // The gather kernels form absolute LDS addresses with the Psumbook at offset 0 of the
+    // workgroup's allocation: a kernel that also had static LDS would have its dynamic part moved.
+    hipFuncAttributes attr;
+    if (hipFuncGetAttributes(&attr, fn) != hipSuccess) return CODEGEMM_LAUNCH_FAILED;
+    if (attr.sharedSizeBytes != 0) return CODEGEMM_UNSUPPORTED;
     if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds) != hipSuccess)
         return CODEGEMM_LAUNCH_FAILED;
     done.emplace_back(fn, dev);
@@ -35,9 +40,10 @@ static uint64_t* g_trace = nullptr;
 extern "C" void codegemm_set_trace(uint64_t* stamps) { g_trace = stamps; }
 #endif
 
-extern "C" int codegemm_gemm(const codegemm_desc* desc, const codegemm_plan* plan, const void* x,
-                             const uint8_t* packed_codes, const void* codebooks, const void* scales,
-                             void* y, void* workspace, size_t workspace_bytes, void* stream)
+// One launch: at most kBatchPerLaunch batch rows.
+static int gemm_launch(const codegemm_desc* desc, const codegemm_plan* plan, const void* x,
+                       const uint8_t* packed_codes, const void* codebooks, const void* scales,
+                       void* y, void* workspace, size_t workspace_bytes, void* stream)
 {
     Geometry g;
     int st = make_geometry(desc, plan, &g);
@@ -95,4 +101,29 @@ extern "C" int codegemm_gemm(const codegemm_desc* desc, const codegemm_plan* pla
         case 4: return launch_gemm_m4(g, p, s);
     }
     return CODEGEMM_UNSUPPORTED;
+}
+
+extern "C" int codegemm_gemm(const codegemm_desc* desc, const codegemm_plan* plan, const void* x,
+                             const uint8_t* packed_codes, const void* codebooks, const void* scales,
+                             void* y, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!desc || desc->batch <= kBatchPerLaunch)
+        return gemm_launch(desc, plan, x, packed_codes, codebooks, scales, y, workspace, workspace_bytes, stream);
+    // A larger batch runs as consecutive launches of up to kBatchPerLaunch rows on the same
+    // stream, sharing the workspace (launches on one stream do not overlap).  Row offsets of
+    // x and y are multiples of 64 bytes, so the alignment of the pointers carries over.
+    Geometry g;
+    int st = make_geometry(desc, plan, &g);
+    if (st) return st;
+    if (!x || !y) return CODEGEMM_INVALID_ARG;
+    const size_t ysize = g.y_fp32 ? sizeof(float) : sizeof(_Float16);
+    for (int b0 = 0; b0 < desc->batch; b0 += kBatchPerLaunch) {
+        codegemm_desc part = *desc;
+        part.batch = desc->batch - b0 < kBatchPerLaunch ? desc->batch - b0 : kBatchPerLaunch;
+        st = gemm_launch(&part, plan, static_cast<const unsigned char*>(x) + (size_t)b0 * g.K * sizeof(_Float16),
+                         packed_codes, codebooks, scales, static_cast<unsigned char*>(y) + (size_t)b0 * g.N * ysize,
+                         workspace, workspace_bytes, stream);
+        if (st) return st;
+    }
+    return CODEGEMM_OK;
 }

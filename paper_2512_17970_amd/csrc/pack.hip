@@ -104,6 +104,35 @@ extern "C" int codegemm_unpack_codes(const codegemm_desc* desc, const codegemm_p
     return hipGetLastError() == hipSuccess ? CODEGEMM_OK : CODEGEMM_LAUNCH_FAILED;
 }
 
+// Host versions: plain loops over the same offset function the kernels use (host pointers, synchronous).
+extern "C" int codegemm_pack_codes_host(const codegemm_desc* desc, const uint8_t* codes, uint8_t* packed)
+{
+    Geometry g;
+    int st = make_geometry(desc, nullptr, &g);
+    if (st) return st;
+    if (!codes || !packed) return CODEGEMM_INVALID_ARG;
+    const int Jpad = g.NKT * kSlots;
+    for (int c = 0; c < g.m; ++c)
+        for (int n = 0; n < g.Npad; ++n)
+            for (int j = 0; j < Jpad; ++j)
+                packed[packed_offset(c, n, j, g.m, g.NKT)] =
+                    (n < g.N && j < g.J) ? codes[((size_t)c * g.N + n) * g.J + j] : (uint8_t)0;
+    return CODEGEMM_OK;
+}
+
+extern "C" int codegemm_unpack_codes_host(const codegemm_desc* desc, const uint8_t* packed, uint8_t* codes)
+{
+    Geometry g;
+    int st = make_geometry(desc, nullptr, &g);
+    if (st) return st;
+    if (!codes || !packed) return CODEGEMM_INVALID_ARG;
+    for (int c = 0; c < g.m; ++c)
+        for (int n = 0; n < g.N; ++n)
+            for (int j = 0; j < g.J; ++j)
+                codes[((size_t)c * g.N + n) * g.J + j] = packed[packed_offset(c, n, j, g.m, g.NKT)];
+    return CODEGEMM_OK;
+}
+
 extern "C" int codegemm_pack_scales(const codegemm_desc* desc, const void* scales, void* packed, void* stream)
 {
     Geometry g;

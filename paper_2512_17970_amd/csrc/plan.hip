@@ -10,7 +10,9 @@ static int validate_desc(const codegemm_desc* d)
     if (d->vec_len != 4 && d->vec_len != 8 && d->vec_len != 16) return CODEGEMM_UNSUPPORTED;
     if (d->num_codebooks < 1 || d->num_codebooks > 4) return CODEGEMM_UNSUPPORTED;
     if (d->code_bits != 8) return CODEGEMM_UNSUPPORTED;
-    if (d->batch > 32) return CODEGEMM_UNSUPPORTED;
+    // Every byte offset the kernels form (a workgroup's code range, a row of x) stays below 2^31.
+    if (d->batch > kMaxBatch || d->in_features > kMaxInFeatures || d->out_features > kMaxOutFeatures)
+        return CODEGEMM_UNSUPPORTED;
     if (d->in_features % d->vec_len) return CODEGEMM_INVALID_ARG;
     if (d->group_size != -1) {
         // one scale per g = v * 2^i weights, groups tiling K exactly
@@ -60,13 +62,14 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
     // Two batch rows: the batch-1 kernel with the code words reused for a second Psumbook, except on
     // large matrices, where the batched kernel wins even with two of its four batch lanes idle
     // (8192->28672: 32.7 -> 25.6 us; 8192^2: 11.4 against 12.0)
-    p->batch_group = d->batch == 1 ? 1 : ((d->batch == 2 && code_positions < 16e6) ? 2 : 4);
+    const int batch = d->batch < kBatchPerLaunch ? d->batch : kBatchPerLaunch;
+    p->batch_group = batch == 1 ? 1 : ((batch == 2 && code_positions < 16e6) ? 2 : 4);
     if (p->batch_group == 4) {
         // LDS- and ALU-bound.  Every workgroup rebuilds the Psumbook of its tiles, and LDS
         // writes are slow, so blocks are 1024 rows tall when there are at least two batch
         // groups to fill the chip with, 512 otherwise; K ranges are cut so that all batch
         // groups together give close to, but not more than, 256 workgroups.
-        const int groups = ceil_div(d->batch, 4);
+        const int groups = ceil_div(batch, 4);
         p->waves = 16;
         p->row_words = groups >= 2 ? 2 : 1;
         if (groups == 1) {
@@ -125,7 +128,7 @@ int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g
     }
     st = validate_plan(d, plan);
     if (st) return st;
-    g->B = d->batch;
+    g->B = d->batch < kBatchPerLaunch ? d->batch : kBatchPerLaunch;   // larger batches run as several launches
     g->K = d->in_features;
     g->N = d->out_features;
     g->v = d->vec_len;
@@ -186,7 +189,16 @@ extern "C" size_t codegemm_workspace_bytes(const codegemm_desc* desc, const code
 {
     Geometry g;
     if (make_geometry(desc, plan, &g)) return 0;
-    return workspace_counter_bytes(g) + (size_t)g.B * g.NKS * g.Npad * sizeof(float);
+    size_t bytes = workspace_counter_bytes(g) + (size_t)g.B * g.NKS * g.Npad * sizeof(float);
+    if (desc->batch > kBatchPerLaunch && desc->batch % kBatchPerLaunch) {
+        // the last launch of a large batch has fewer rows and, under the default plan, other K ranges
+        codegemm_desc tail = *desc;
+        tail.batch = desc->batch % kBatchPerLaunch;
+        if (make_geometry(&tail, plan, &g)) return 0;
+        const size_t b2 = workspace_counter_bytes(g) + (size_t)g.B * g.NKS * g.Npad * sizeof(float);
+        if (b2 > bytes) bytes = b2;
+    }
+    return bytes;
 }
 
 extern "C" size_t codegemm_packed_codes_bytes(const codegemm_desc* desc, const codegemm_plan* plan)

@@ -100,7 +100,7 @@ extern "C" int codegemm_psumbook_build(const codegemm_desc* desc, const void* x,
     if (misaligned(x) || misaligned(codebooks) || misaligned(psumbook)) return CODEGEMM_INVALID_ARG;
     const _Float16* xh = static_cast<const _Float16*>(x);
     const _Float16* cb = static_cast<const _Float16*>(codebooks);
-    const long rows = (long)g.B * g.J;
+    const long rows = (long)desc->batch * g.J;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (use_mfma) {
         const long tiles = ((rows + 31) / 32) * g.m * 8;

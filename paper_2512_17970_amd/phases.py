@@ -33,8 +33,6 @@ def _trace_lib() -> ctypes.CDLL:
     lib.codegemm_gemm.restype = i
     lib.codegemm_set_trace.argtypes = [vp]
     lib.codegemm_set_trace.restype = None
-    lib.codegemm_probe_load_issue.argtypes = [vp, sz, i, i, i, vp, vp]
-    lib.codegemm_probe_load_issue.restype = i
     return lib
 
 
@@ -89,44 +87,4 @@ def phase_table(torch, desc, plan, x, packed_codes, codebooks, scales, y, worksp
             rel = (col[ok] - t0) * TICK_US
             rows.append({"slot": slot, "phase": label, "workgroups": int(ok.sum()),
                          "mean_us": float(rel.mean()), "min_us": float(rel.min()), "max_us": float(rel.max())})
-    return rows
-
-
-def load_issue_probe(torch, workgroups: int = 256, configs=((16, 1), (16, 2), (16, 4), (16, 8), (8, 2), (8, 4), (8, 8)),
-                     reps: int = 3) -> List[Dict]:
-    """How many vector loads a compute unit keeps outstanding (codegemm_probe_load_issue of the diagnostic
-    build): for every (wavefronts, 16-byte loads per lane) pair, warm (the same stretch of memory again) and
-    cold (a stretch of a 1 GiB buffer not touched for at least 1 GiB of other reads), the clocks after which
-    the first and the last wavefront of a workgroup had issued all its loads, had its first datum and had all
-    its data; means over the workgroups of the last of `reps` launches."""
-    lib = _trace_lib()
-    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
-    pool_bytes = 1 << 30
-    pool = torch.empty(pool_bytes, dtype=torch.uint8, device="cuda").fill_(1)
-    cursor = 0
-    rows = []
-    for cold in (False, True):
-        for waves, nl in configs:
-            per_launch = workgroups * waves * 64 * 16 * nl
-            out = torch.zeros(workgroups * waves * 4 + 1, dtype=torch.int64, device="cuda")
-            for _ in range(reps):
-                if cold:
-                    if cursor + per_launch + 16 > pool_bytes:
-                        cursor = 0
-                    src, cursor = pool[cursor:], cursor + per_launch
-                else:
-                    src = pool[pool_bytes - per_launch - 4096:]
-                st = lib.codegemm_probe_load_issue(binding._ptr(src), src.numel(), workgroups, waves, nl,
-                                                   binding._ptr(out), stream)
-                if st:
-                    raise binding.CodegemmError(st, "codegemm_probe_load_issue")
-                torch.cuda.synchronize()
-            t = out[:-1].cpu().numpy().astype("float64").reshape(workgroups, waves, 4)
-            mhz = float((t[:, :, 2] / t[:, :, 3]).mean() * 100.0)
-            rows.append({"cold": cold, "waves": waves, "loads_per_lane": nl, "bytes_per_workgroup": waves * 64 * 16 * nl,
-                         "issue_first_wave_clk": float(t[:, :, 0].min(axis=1).mean()),
-                         "issue_last_wave_clk": float(t[:, :, 0].max(axis=1).mean()),
-                         "first_datum_first_wave_clk": float(t[:, :, 1].min(axis=1).mean()),
-                         "first_datum_last_wave_clk": float(t[:, :, 1].max(axis=1).mean()),
-                         "all_data_clk": float(t[:, :, 2].max(axis=1).mean()), "shader_mhz": mhz})
     return rows

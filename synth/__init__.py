@@ -64,7 +64,9 @@ def workloads() -> Dict[int, List[Case]]:
     6 a sweep of the normalisation group size g at 8192->28672, 7 and 8 the 8B and 70B
     shapes in the formats the paper's latency table uses (m1v4g128, m2v8g128), 9 and 10 the
     same two decoder blocks with fused projections (QKV as one matrix, gate and up as one),
-    11 the five formats of the paper's average-bits table (all close to 2 bits) at 8192->28672."""
+    11 the five formats of the paper's average-bits table (all close to 2 bits) at 8192->28672,
+    12 and 13 the (batch, N, K) grid of the paper's appendix table of kernel latencies across
+    problem sizes (batch 1, 4, 8 at nine shapes from 2048^2 to 8192->28672) for m2v8g128 and m1v4g128."""
     out: Dict[int, List[Case]] = {}
     out[1] = [_case(1, 0, 512, 512, 8, 1, 1)]
     out[2] = [_case(2, i, K, N, 4, 1, 1) for i, (K, N) in
@@ -91,6 +93,11 @@ def workloads() -> Dict[int, List[Case]]:
                enumerate([(8192, 10240), (8192, 8192), (8192, 57344), (28672, 8192)])]
     out[11] = [_case(11, i, 8192, 28672, v, m, 1, g) for i, (v, m, g) in
                enumerate([(4, 1, -1), (8, 2, -1), (16, 4, -1), (8, 1, 16), (16, 3, 32)])]
+    grid = [(2048, 2048), (2048, 8192), (8192, 2048), (4096, 4096), (4096, 14336), (14336, 4096),
+            (8192, 8192), (8192, 28672), (28672, 8192)]                     # (K, N)
+    for cfg, (v, m) in ((12, (8, 2)), (13, (4, 1))):
+        out[cfg] = [_case(cfg, 3 * si + bi, K, N, v, m, B, 128)
+                    for si, (K, N) in enumerate(grid) for bi, B in enumerate([1, 4, 8])]
     return out
 
 

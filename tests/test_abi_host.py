@@ -34,11 +34,11 @@ def test_trace_library_exports_the_abi_and_the_trace_hook():
     text = open(os.path.join(ROOT, "include", "codegemm_trace.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     extra = sorted(set(re.findall(r"\b(codegemm_[a-z_]+)\s*\(", text)))
-    assert extra == ["codegemm_probe_load_issue", "codegemm_set_trace"]
+    assert extra == ["codegemm_set_trace"]
     lib = ctypes.CDLL(phases.TRACE_LIB_PATH)
     for s in header_symbols() + extra:
         assert hasattr(lib, s), s
-    assert not hasattr(cg.load(), "codegemm_set_trace") and not hasattr(cg.load(), "codegemm_probe_load_issue")
+    assert not hasattr(cg.load(), "codegemm_set_trace")
 
 
 def test_phases_workgroup_count_matches_the_plan():
@@ -47,6 +47,41 @@ def test_phases_workgroup_count_matches_the_plan():
     assert phases.workgroups(d, cg.Plan.make(16, 2, 4, 1)) == 224
     assert phases.workgroups(d, cg.Plan.make(8, 1, 1000, 1)) == 224 * 32
     assert phases.workgroups(cg.Desc.make(32, 4096, 14336, 8, 2), cg.Plan.make(16, 2, 2, 4)) == 28
+
+
+def test_host_pack_is_the_documented_layout_and_roundtrips():
+    """codegemm_pack_codes_host / codegemm_unpack_codes_host run without a GPU: checked against the
+    oracle's independent description of the layout (itself pinned byte by byte in
+    test_pack_layout_pin.py) and against each other."""
+    import numpy as np
+    from oracle.pack_layout import pack_reference
+    rng = np.random.default_rng(5)
+    for (N, J, v, m) in [(130, 33, 8, 1), (129, 65, 8, 2), (257, 31, 4, 3), (200, 40, 16, 4), (1, 1, 4, 2), (512, 64, 8, 2)]:
+        codes = rng.integers(0, 256, size=(m, N, J), dtype=np.uint8)
+        d = cg.Desc.make(1, J * v, N, v, m)
+        nbytes = cg.codegemm_packed_codes_bytes(d)
+        packed = np.full(nbytes + 64, 0x5A, np.uint8)
+        cg.codegemm_pack_codes_host(d, codes, packed[:nbytes])
+        assert np.array_equal(packed[:nbytes], pack_reference(codes))
+        assert np.all(packed[nbytes:] == 0x5A)
+        back = np.full_like(codes, 0x77)
+        cg.codegemm_unpack_codes_host(d, packed[:nbytes], back)
+        assert np.array_equal(back, codes)
+    with pytest.raises(cg.CodegemmError):
+        cg.codegemm_pack_codes_host(cg.Desc.make(1, 510, 512, 8, 1), np.zeros(8, np.uint8), np.zeros(8, np.uint8))
+
+
+def test_large_batches_are_accepted_and_sized_by_their_largest_launch():
+    """More than 32 batch rows run as consecutive launches of up to 32: the workspace is that of the larger
+    of a 32-row launch and the remainder's, the default plan that of a 32-row launch."""
+    d32, d70, d1 = cg.Desc.make(32, 4096, 4096, 8, 2), cg.Desc.make(70, 4096, 4096, 8, 2), cg.Desc.make(6, 4096, 4096, 8, 2)
+    assert cg.codegemm_workspace_bytes(d70) == max(cg.codegemm_workspace_bytes(d32), cg.codegemm_workspace_bytes(d1))
+    p70, p32 = cg.codegemm_default_plan(d70), cg.codegemm_default_plan(d32)
+    assert (p70.waves, p70.row_words, p70.k_splits, p70.batch_group) == (p32.waves, p32.row_words, p32.k_splits, p32.batch_group)
+    assert cg.codegemm_packed_codes_bytes(d70) == cg.codegemm_packed_codes_bytes(d32)
+    assert cg.codegemm_workspace_bytes(cg.Desc.make(65536, 512, 512, 8, 1)) == 0
+    assert cg.codegemm_workspace_bytes(cg.Desc.make(1, 8 << 20, 512, 8, 1)) == 0       # K beyond 2^22
+    assert cg.codegemm_workspace_bytes(cg.Desc.make(1, 512, (1 << 24) + 1, 8, 1)) == 0
 
 
 def test_status_strings():
@@ -93,7 +128,7 @@ def test_invalid_descriptors_are_rejected():
               cg.Desc.make(1, 512, 512, 32, 1), cg.Desc.make(1, 512, 512, 2, 1), cg.Desc.make(1, 512, 512, 8, 5), cg.Desc.make(1, 512, 512, 8, 1, b=4),
               cg.Desc.make(1, 512, 512, 8, 1, g=12), cg.Desc.make(1, 512, 512, 8, 1, g=4),
               cg.Desc.make(1, 512, 512, 8, 1, g=48), cg.Desc.make(1, 8 * 40, 512, 8, 1, g=128), cg.Desc.make(1, 512, 512, 8, 1, g=0),
-              cg.Desc.make(33, 512, 512, 8, 1)):
+              cg.Desc.make(65536, 512, 512, 8, 1)):
         assert cg.codegemm_workspace_bytes(d) == 0
         assert cg.codegemm_packed_codes_bytes(d) == 0
         with pytest.raises(cg.CodegemmError):

@@ -10,7 +10,7 @@ from oracle.pack_layout import pack_reference
 pytestmark = pytest.mark.gpu
 
 cg = pytest.importorskip("paper_2512_17970_amd")
-from gpu_util import DeviceLayer, check_against_oracle, dev, stream  # noqa: E402
+from gpu_util import DeviceLayer, Guarded, check_against_oracle, dev, stream  # noqa: E402
 
 
 def say(msg):
@@ -153,9 +153,11 @@ def test_pack_scales_matches_documented_layout():
                     blockvals = np.zeros(128, np.float16)
                     blockvals[ok] = inp.scales[rows[ok], first // g]
                     want[rg, kt, q] = blockvals.reshape(16, 8)
-        packed = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        guard = Guarded(nbytes)
+        packed = guard.t
         cg.codegemm_pack_scales(desc, dev(inp.scales), packed, stream())
         torch.cuda.synchronize()
+        assert guard.intact()
         got = packed.cpu().numpy().view(np.float16).reshape(want.shape)
         assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
 
@@ -178,13 +180,24 @@ def test_pack_matches_documented_layout_and_roundtrips():
         want = pack_reference(inp.codes)
         assert nbytes == want.size
         codes_d = dev(inp.codes)
-        packed = torch.full((nbytes,), 0xAB, dtype=torch.uint8, device="cuda")
+        gp, gb = Guarded(nbytes), Guarded(inp.codes.size)
+        packed = gp.t
+        packed.fill_(0xAB)
         cg.codegemm_pack_codes(desc, None, codes_d, packed, stream())
-        back = torch.full_like(codes_d, 0xCD)
+        back = gb.view(torch.uint8, codes_d.shape)
+        back.fill_(0xCD)
         cg.codegemm_unpack_codes(desc, None, packed, back, stream())
         torch.cuda.synchronize()
+        assert gp.intact() and gb.intact()
         assert np.array_equal(packed.cpu().numpy(), want)
         assert torch.equal(back, codes_d)
+        # the host versions give the same bytes as the device kernels
+        host_packed = np.full(nbytes, 0xEE, np.uint8)
+        cg.codegemm_pack_codes_host(desc, inp.codes, host_packed)
+        assert np.array_equal(host_packed, packed.cpu().numpy())
+        host_back = np.full_like(inp.codes, 0xDD)
+        cg.codegemm_unpack_codes_host(desc, packed.cpu().numpy(), host_back)
+        assert np.array_equal(host_back, inp.codes)
 
 
 @pytest.mark.parametrize("use_mfma", [False, True])
@@ -251,12 +264,14 @@ def test_diagnostic_build_gives_the_same_output_and_a_monotone_timeline():
                        (synth.custom_case(8 * 32 * 4, 1100, 8, 2, 6, seed=72), cg.Plan.make(16, 1, 2, 4))):
         say(f"[phases] {case.name} {plan}")
         inp = synth.generate(case)
+        y_ref, T = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
         layer = DeviceLayer(inp, plan=plan)
         y_prod = layer.gemm()
         torch.cuda.synchronize()
         y = layer.new_y()
         rows = phases.phase_table(torch, layer.desc, layer.plan, layer.x, layer.packed, layer.codebooks, layer.gemm_scales,
                                   y, layer.ws, layer.ws_bytes, warmup=1)
+        check_against_oracle(y.cpu().numpy(), y_ref, T, f"trace build {case.name}")
         assert torch.equal(y, y_prod)
         by = {r["phase"]: r for r in rows}
         n = phases.workgroups(layer.desc, layer.plan)
@@ -270,20 +285,10 @@ def test_diagnostic_build_gives_the_same_output_and_a_monotone_timeline():
         assert 0 < by["output stored"]["max_us"] < 1000
 
 
-def test_load_issue_probe_runs_and_its_stamps_are_ordered():
-    """The probe of the diagnostic build: stamps of a wavefront are ordered (issued <= first datum <= all
-    data), and a workgroup that asks for 128 KB gets its last loads out later than one that asks for 16 KB."""
-    from paper_2512_17970_amd import phases
-    rows = phases.load_issue_probe(torch, workgroups=64, configs=((16, 1), (16, 8)), reps=2)
-    assert len(rows) == 4
-    for r in rows:
-        say(f"[probe] {r}")
-        assert 0 < r["issue_first_wave_clk"] <= r["issue_last_wave_clk"] <= r["all_data_clk"]
-        assert r["first_datum_first_wave_clk"] <= r["first_datum_last_wave_clk"] <= r["all_data_clk"]
-        assert 500 < r["shader_mhz"] < 5000
-    small = [r for r in rows if r["loads_per_lane"] == 1 and not r["cold"]][0]
-    large = [r for r in rows if r["loads_per_lane"] == 8 and not r["cold"]][0]
-    assert large["issue_last_wave_clk"] > small["issue_last_wave_clk"]
+@pytest.mark.parametrize("B,K,N,v,m,g", [(70, 1024, 600, 8, 2, -1), (33, 4 * 200, 257, 4, 1, 32), (64, 2048, 130, 16, 3, -1)])
+def test_batches_above_one_launch(B, K, N, v, m, g):
+    """More than 32 batch rows: consecutive launches of up to 32 rows that share the workspace."""
+    run_case(synth.custom_case(K, N, v, m, B, seed=606 + B, g=g))
 
 
 def test_random_formats_shapes_and_plans():
