@@ -42,6 +42,8 @@ def _load() -> ctypes.CDLL:
         lib = ctypes.CDLL(_LIB)
         i, p = ctypes.c_int, ctypes.c_void_p
         lib.oracle_num_threads.restype = i
+        lib.oracle_set_num_threads.argtypes = [i]
+        lib.oracle_set_num_threads.restype = None
         lib.oracle_dequantize.argtypes = [i, i, i, i, i, p, p, p, p]
         lib.oracle_dequantize.restype = i
         lib.oracle_gemm.argtypes = [i, i, i, i, i, i, p, p, p, p, p, p]
@@ -54,6 +56,11 @@ def _load() -> ctypes.CDLL:
 
 def num_threads() -> int:
     return int(_load().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads the following calls use (for timing the oracle on one core)."""
+    _load().oracle_set_num_threads(int(n))
 
 
 def _c(a: np.ndarray, dtype) -> np.ndarray:

@@ -71,6 +71,16 @@ int oracle_num_threads(void)
 #endif
 }
 
+/* Threads the following calls use (n >= 1); only how the rows are shared out changes, no sum does. */
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 static int bad_shape(int N, int K, int v, int m)
 {
     return N < 1 || K < 1 || v < 1 || m < 1 || (K % v) != 0;

@@ -85,12 +85,16 @@ class DeviceLayer:
         for k in [k for k in self.guards if k.startswith("y@") and k != f"y@{y.data_ptr():x}"]:
             del self.guards[k]
 
-    def gemm(self, y=None):
+    def gemm(self, y=None, check=True):
+        """check=False: only enqueue (for calls recorded into a HIP graph, where nothing may
+        synchronise); the caller runs check_guards() after the replay."""
         y = self.new_y() if y is None else y
-        self._forget_other_outputs(y)
+        if check:
+            self._forget_other_outputs(y)
         cg.codegemm_gemm(self.desc, self.plan, self.x, self.packed, self.codebooks, self.gemm_scales, y,
                          self.ws, self.ws_bytes, stream())
-        self.check_guards("codegemm_gemm")
+        if check:
+            self.check_guards("codegemm_gemm")
         return y
 
     def dequant(self, y=None):
