@@ -199,6 +199,25 @@ int codegemm_gemm(const codegemm_desc *desc, const codegemm_plan *plan,
                   void *stream);
 
 /*
+ * codegemm_gemm for callers that cannot allocate device memory or carry a
+ * workspace around: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same computation, same kernels and the same
+ * bits in y as codegemm_gemm; the workspace is an array of
+ * codegemm_static_workspace_limit() bytes (8 MiB) that lives inside the loaded
+ * library, one per GPU, until the process ends.  The call allocates nothing.
+ * Returns CODEGEMM_WORKSPACE_TOO_SMALL when codegemm_workspace_bytes(desc, plan)
+ * exceeds that limit (about batch * k_splits * N > 2 million).  The first call on
+ * a device looks the array up and clears its ticket counters on `stream`; make
+ * that call outside graph capture.  All calls on one GPU share the array: two
+ * that overlap in time (different streams, or graphs replayed concurrently)
+ * race; calls on one stream, of any shapes and plans, do not.
+ */
+size_t codegemm_static_workspace_limit(void);
+int codegemm_gemm_static(const codegemm_desc *desc, const codegemm_plan *plan,
+                         const void *x, const uint8_t *packed_codes, const void *codebooks,
+                         const void *scales, void *y, void *stream);
+
+/*
  * Dequantization-based comparator (Section 2.3: the whole codebook sits in LDS,
  * each code fetches its centroid vector, which is multiplied with the matching
  * activations; O(N*B*K) multiply-adds).  Same result as codegemm_gemm up to

@@ -12,4 +12,5 @@ from .binding import (  # noqa: F401
     codegemm_packed_scales_bytes,
     codegemm_pack_scales,
     codegemm_pack_codes_host, codegemm_unpack_codes_host,
+    codegemm_gemm_static, codegemm_static_workspace_limit,
 )

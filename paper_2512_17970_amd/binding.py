@@ -24,6 +24,7 @@ EXPORTS = [
     "codegemm_pack_codes_host", "codegemm_unpack_codes_host",
     "codegemm_packed_scales_bytes", "codegemm_pack_scales",
     "codegemm_psumbook_build", "codegemm_gemm", "codegemm_dequant_gemm", "codegemm_status_string",
+    "codegemm_gemm_static", "codegemm_static_workspace_limit",
 ]
 
 
@@ -97,6 +98,10 @@ def load() -> ctypes.CDLL:
     lib.codegemm_psumbook_build.restype = i
     lib.codegemm_gemm.argtypes = [dp, pp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.codegemm_gemm.restype = i
+    lib.codegemm_gemm_static.argtypes = [dp, pp, vp, vp, vp, vp, vp, vp]
+    lib.codegemm_gemm_static.restype = i
+    lib.codegemm_static_workspace_limit.argtypes = []
+    lib.codegemm_static_workspace_limit.restype = sz
     lib.codegemm_dequant_gemm.argtypes = [dp, vp, vp, vp, vp, vp, vp]
     lib.codegemm_dequant_gemm.restype = i
     lib.codegemm_status_string.argtypes = [i]
@@ -192,6 +197,15 @@ def codegemm_gemm(desc: Desc, plan: Optional[Plan], x, packed_codes, codebooks, 
     _check(load().codegemm_gemm(ctypes.byref(desc), _plan(plan), _ptr(x), _ptr(packed_codes), _ptr(codebooks),
                                 _ptr(scales), _ptr(y), _ptr(workspace), workspace_bytes,
                                 ctypes.c_void_p(stream)), "codegemm_gemm")
+
+
+def codegemm_static_workspace_limit() -> int:
+    return int(load().codegemm_static_workspace_limit())
+
+
+def codegemm_gemm_static(desc: Desc, plan: Optional[Plan], x, packed_codes, codebooks, scales, y, stream: int = 0) -> None:
+    _check(load().codegemm_gemm_static(ctypes.byref(desc), _plan(plan), _ptr(x), _ptr(packed_codes), _ptr(codebooks),
+                                       _ptr(scales), _ptr(y), ctypes.c_void_p(stream)), "codegemm_gemm_static")
 
 
 def codegemm_dequant_gemm(desc: Desc, x, codes, codebooks, scales, y, stream: int = 0) -> None:

@@ -34,6 +34,36 @@ int set_max_lds(const void* fn, size_t bytes)
 
 using namespace cg;
 
+// Workspace of codegemm_gemm_static: one array per GPU, held by the loaded library until
+// the process ends.  In host code the array's name only stands for the symbol; its device
+// address is looked up once per device and used from then on.
+constexpr size_t kStaticWorkspaceBytes = 8u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device; on first use there, the ticket
+// counters at its start are cleared on `stream` (a fill kernel), ahead of the caller's launch.
+int static_workspace(void** out, hipStream_t stream)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CODEGEMM_LAUNCH_FAILED;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return CODEGEMM_LAUNCH_FAILED;
+        const int st = codegemm_workspace_init(ptr, (size_t)kCounterAreaWords * sizeof(uint32_t), stream);
+        if (st) return st;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return CODEGEMM_OK;
+}
+}  // namespace
+
 #ifdef CODEGEMM_TRACE
 #include "codegemm_trace.h"
 static uint64_t* g_trace = nullptr;
@@ -126,4 +156,23 @@ extern "C" int codegemm_gemm(const codegemm_desc* desc, const codegemm_plan* pla
         if (st) return st;
     }
     return CODEGEMM_OK;
+}
+
+extern "C" size_t codegemm_static_workspace_limit(void) { return kStaticWorkspaceBytes; }
+
+extern "C" int codegemm_gemm_static(const codegemm_desc* desc, const codegemm_plan* plan, const void* x,
+                                    const uint8_t* packed_codes, const void* codebooks, const void* scales,
+                                    void* y, void* stream)
+{
+    const size_t need = codegemm_workspace_bytes(desc, plan);
+    if (need == 0) {
+        Geometry g;
+        const int st = make_geometry(desc, plan, &g);
+        return st ? st : CODEGEMM_INVALID_ARG;
+    }
+    if (need > kStaticWorkspaceBytes) return CODEGEMM_WORKSPACE_TOO_SMALL;
+    void* ws = nullptr;
+    const int st = static_workspace(&ws, static_cast<hipStream_t>(stream));
+    if (st) return st;
+    return codegemm_gemm(desc, plan, x, packed_codes, codebooks, scales, y, ws, kStaticWorkspaceBytes, stream);
 }
