@@ -53,6 +53,10 @@ def parse():
                     help="time every launch plan shape x K-split count for every shape of the workload (cold)")
     ap.add_argument("--psumbook", action="store_true",
                     help="instead of the GEMM: time the stand-alone Psumbook build (vector ALU and MFMA) at batch 1, 8, 32")
+    ap.add_argument("--ablate", type=int, default=0,
+                    help="time an ablation build of the library instead (libcodegemm_ablate_<mask>.so; outputs are wrong on "
+                         "purpose): 2 no gather, 4 no Psumbook build after the first, 8 no exchange between workgroups; "
+                         "6, 8 and 14 are built by default")
     ap.add_argument("--plan", default="", help="override plan for every shape: waves,row_words,k_splits[,batch_group]")
     return ap.parse_args()
 
@@ -314,6 +318,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
+    if args.ablate:
+        from paper_2512_17970_amd import build as cg_build
+        cg.binding.use_library(cg_build.ablate_lib(args.ablate))
+        args.no_cpu_baseline = True
     cg.load()
     if args.psumbook:
         psumbook_bench(torch, cg, synth)
@@ -374,6 +382,9 @@ def main():
                    "cold_copies_bytes_per_shape": COLD_BYTES},
         "roofline": roofline,
     }
+    if args.ablate:
+        out["ablation"] = {"mask": args.ablate, "note": "diagnostic build with parts of the kernel compiled out; "
+                           "outputs are wrong on purpose, the number is a ceiling study, not a result"}
     detail = None
     if not args.no_detail:
         log("per-shape (min of 5 x 200 calls):")

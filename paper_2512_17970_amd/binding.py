@@ -63,6 +63,15 @@ def lib_path() -> str:
     return _LIB_PATH
 
 
+def use_library(path: str) -> None:
+    """Makes load() take another build of the library with the same ABI (a diagnostic build such as
+    libcodegemm_ablate_<mask>.so).  Must be called before the first load()."""
+    global _LIB_PATH
+    if _lib is not None:
+        raise RuntimeError("the library is already loaded")
+    _LIB_PATH = os.path.abspath(path)
+
+
 def load() -> ctypes.CDLL:
     """Loads libcodegemm.so; raises if it has not been built (no fallback exists)."""
     global _lib

@@ -37,6 +37,14 @@
 
 #include "cg_common.h"
 
+// Ablation builds (diagnostic libraries libcodegemm_ablate_<mask>.so, never the production one)
+// compile parts of the batch-1 gather kernel out to show what each costs on top of the code
+// stream.  Their outputs are wrong on purpose.  Mask bits: 1 gather without its LDS reads,
+// 2 no gather at all, 4 no Psumbook build after the first, 8 no exchange between workgroups.
+#ifndef CODEGEMM_ABLATE
+#define CODEGEMM_ABLATE 0
+#endif
+
 namespace cg {
 
 struct GemmParams {
@@ -214,7 +222,12 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
         else static_cast<_Float16*>(p.y)[(size_t)row * p.N + nn] = (_Float16)val;
     };
 
-    if (p.NKS == 1) {
+#if CODEGEMM_ABLATE & 8
+    const bool single = true;          // ablation build: no exchange between workgroups, every K range stores y
+#else
+    const bool single = p.NKS == 1;
+#endif
+    if (single) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             const int o = tid + i * NT;
@@ -426,7 +439,15 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
         for (int q = 0; q < RPL; ++q)
             dst[q] = __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(s_rsrc[GS ? q : 0], u * p.GPU * 256 + s_off, 0, 0));
     };
+#if CODEGEMM_ABLATE & 4
+    bool first_build = true;
+#endif
     auto build = [&](float* buf, frag_t xf) {
+#if CODEGEMM_ABLATE & 4
+        // ablation build: only the first Psumbook is built; the activations are still consumed
+        if (!first_build) { asm volatile("" :: "v"(xf)); return; }
+        first_build = false;
+#endif
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
             const int tile = wave + i * NW;
@@ -510,6 +531,22 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
                                                  ((uint32_t)(L::superplane(c) + par * L::kSuperplanes) << 16);
                             const uint32_t lo = w[d][q][2 * c], hi = w[d][q][2 * c + 1];
                             const half8_t sv = sc[GS ? d % DS : 0][q];
+#if CODEGEMM_ABLATE & 2
+                            // ablation build: the code words are consumed, nothing is gathered
+                            acc[bb][q][c & 7] += __builtin_bit_cast(float, (lo ^ hi) & 0x007fffffu);
+                            (void)off; (void)sv;
+                            continue;
+#elif CODEGEMM_ABLATE & 1
+                            // ablation build: address arithmetic and additions stay, the LDS reads go
+#define CG_FAKE(k, wd) __builtin_bit_cast(float, __builtin_amdgcn_perm(wd, off, 0x0c020000u | ((4u + k) << 8)) & 0x007fffffu)
+                            acc[bb][q][0] += CG_FAKE(0, lo); acc[bb][q][1] += CG_FAKE(1, lo);
+                            acc[bb][q][2] += CG_FAKE(2, lo); acc[bb][q][3] += CG_FAKE(3, lo);
+                            acc[bb][q][4] += CG_FAKE(0, hi); acc[bb][q][5] += CG_FAKE(1, hi);
+                            acc[bb][q][6] += CG_FAKE(2, hi); acc[bb][q][7] += CG_FAKE(3, hi);
+#undef CG_FAKE
+                            (void)sv;
+                            continue;
+#endif
                             acc[bb][q][0] = accumulate<GS>(acc[bb][q][0], psum_at<0>(lo, off), sv[0]);
                             acc[bb][q][1] = accumulate<GS>(acc[bb][q][1], psum_at<1>(lo, off), sv[1]);
                             acc[bb][q][2] = accumulate<GS>(acc[bb][q][2], psum_at<2>(lo, off), sv[2]);
