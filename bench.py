@@ -57,19 +57,26 @@ def parse():
                     help="time an ablation build of the library instead (libcodegemm_ablate_<mask>.so; outputs are wrong on "
                          "purpose): 2 no gather, 4 no Psumbook build after the first, 8 no exchange between workgroups; "
                          "6, 8 and 14 are built by default")
-    ap.add_argument("--plan", default="", help="override plan for every shape: waves,row_words,k_splits[,batch_group]")
+    ap.add_argument("--plan", default="", help="override plan for every shape: waves,row_words,k_splits[,batch_group[,psum_dtype]] (psum_dtype 1 = fp16 Psumbook)")
+    ap.add_argument("--psum-fp16", action="store_true",
+                    help="every shape's default plan with the Psumbook stored as fp16 (batch 1; the group-scale shapes that "
+                         "default to 16 wavefronts x 2 row words run with 1 row word)")
     return ap.parse_args()
 
 
 class Layer:
     """One quantized layer on the GPU with R rotating copies of its packed codes."""
 
-    def __init__(self, cg, torch, synth, case, plan_override, copies_bytes=COLD_BYTES):
+    def __init__(self, cg, torch, synth, case, plan_override, copies_bytes=COLD_BYTES, psum_fp16=False):
         self.cg, self.torch, self.case = cg, torch, case
         inp = synth.generate(case)
         self.inp = inp
         self.desc = cg.Desc.make(case.B, case.K, case.N, case.v, case.m, g=case.g)
         self.plan = plan_override if plan_override is not None else cg.codegemm_default_plan(self.desc)
+        if psum_fp16 and plan_override is None:
+            p = self.plan
+            rw = 1 if (case.g > 0 and p.waves == 16) else min(p.row_words, 2)
+            self.plan = cg.Plan.make(p.waves, rw, p.k_splits, 1, 1)
         dev = lambda a: torch.from_numpy(a).cuda()
         self.x, self.codes = dev(inp.x), dev(inp.codes)
         self.codebooks, self.scales = dev(inp.codebooks), dev(inp.scales)
@@ -274,21 +281,22 @@ def sweep_report(torch, cg, synth, cases, launch):
                 ks = max(1, min(nkt, target // nblk))
                 cands.add(-(-nkt // -(-nkt // ks)))
             for ks in sorted(cands):
-                plan = cg.Plan.make(waves, rw, ks, bg)
+              for psum in ((0, 1) if bg == 1 else (0,)):                # Psumbook stored as fp32 / fp16
+                plan = cg.Plan.make(waves, rw, ks, bg, psum)
                 if cg.codegemm_workspace_bytes(d, plan) == 0:
                     continue                                            # plan not offered for this format
                 L = Layer(cg, torch, synth, case, plan, copies_bytes=COLD_BYTES // 2)
                 call = graph_of(torch, L.gemm, 50).replay if launch == "graph" else (lambda L=L: [L.gemm() for _ in range(50)])
                 call(); call()
                 us = min(time_region(torch, call, 1) for _ in range(4)) * 1e3 / 50
-                res.append({"waves": waves, "row_words": rw, "k_splits": ks, "batch_group": bg,
+                res.append({"waves": waves, "row_words": rw, "k_splits": ks, "batch_group": bg, "psum_dtype": "fp16" if psum else "fp32",
                             "workgroups": nblk * ks, "us_cold": us})
-                log(f"  {case.name} waves={waves} row_words={rw} k_splits={ks} workgroups={nblk * ks}: {us:.2f} us")
+                log(f"  {case.name} waves={waves} row_words={rw} k_splits={ks} psum={'fp16' if psum else 'fp32'} workgroups={nblk * ks}: {us:.2f} us")
                 del L
                 torch.cuda.empty_cache()
         res.sort(key=lambda r: r["us_cold"])
         out[case.name] = {"default": repr(default), "plans": res}
-        log(f"BEST {case.name}: " + ", ".join(f"({r['waves']},{r['row_words']},{r['k_splits']}) {r['us_cold']:.2f}" for r in res[:3])
+        log(f"BEST {case.name}: " + ", ".join(f"({r['waves']},{r['row_words']},{r['k_splits']},{r['psum_dtype']}) {r['us_cold']:.2f}" for r in res[:3])
             + f"   default {default}")
     print(json.dumps({"sweep": out}))
 
@@ -339,7 +347,7 @@ def main():
     if args.sweep:
         sweep_report(torch, cg, synth, cases, args.launch)
         return
-    layers = [Layer(cg, torch, synth, c, plan_override) for c in cases]
+    layers = [Layer(cg, torch, synth, c, plan_override, psum_fp16=args.psum_fp16) for c in cases]
     torch.cuda.synchronize()
     if args.phases:
         phases_report(torch, cg, layers)
@@ -376,7 +384,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{key}: " + ", ".join(c.name for c in cases),
-                   "calls_per_step": len(layers), "operands": "f16 x, codebooks, scales; u8 codes; f32 Psumbook and accumulation; f16 y", "us_per_step": ms_per_step * 1e3,
+                   "calls_per_step": len(layers), "operands": f"f16 x, codebooks, scales; u8 codes; {'f16' if args.psum_fp16 else 'f32'} Psumbook, f32 accumulation; f16 y", "us_per_step": ms_per_step * 1e3,
                    "timed_runs": len(runs), "us_per_step_min": min(runs) / args.steps * 1e3,
                    "us_per_step_max": max(runs) / args.steps * 1e3, "launch": args.launch,
                    "cold_copies_bytes_per_shape": COLD_BYTES},

@@ -94,8 +94,20 @@ typedef struct codegemm_plan {
                             /* workspace by the last workgroup to finish                               */
     int32_t batch_group;    /* batch rows handled per pass over the codes: 1, 2 or 4.  4 selects the  */
                             /* batched kernel (batch axis innermost in the Psumbook, 128-bit gathers) */
-    int32_t reserved[4];    /* must be zero */
+    int32_t psum_dtype;     /* number type the Psumbook is stored in (LDS): 0 = fp32 (default, exact     */
+                            /* fp16 x fp16 products summed in fp32), 1 = fp16 (each partial sum rounded  */
+                            /* to nearest-even fp16 after its fp32 accumulation; accumulation over K     */
+                            /* stays fp32).  fp16 halves the LDS bytes written per unit and adds about   */
+                            /* 3e-4 relative error to y; needs batch_group = 1, row_words <= 2, and with  */
+                            /* group scales not (waves 16, row_words 2).                                 */
+                            /* codegemm_default_plan never chooses it.                                    */
+    int32_t reserved[3];    /* must be zero */
 } codegemm_plan;
+
+enum {
+    CODEGEMM_PSUM_FP32 = 0,
+    CODEGEMM_PSUM_FP16 = 1
+};
 
 /* Fills *plan with the library's choice for this problem.  Host only, no GPU work. */
 int codegemm_default_plan(const codegemm_desc *desc, codegemm_plan *plan);

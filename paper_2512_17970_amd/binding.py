@@ -17,6 +17,7 @@ _LIB_PATH = os.path.join(_PKG, "libcodegemm.so")
 _lib: Optional[ctypes.CDLL] = None
 
 FLAG_Y_FP32 = 1
+PSUM_FP32, PSUM_FP16 = 0, 1
 
 EXPORTS = [
     "codegemm_default_plan", "codegemm_workspace_bytes", "codegemm_packed_codes_bytes",
@@ -48,15 +49,16 @@ class Desc(ctypes.Structure):
 class Plan(ctypes.Structure):
     """codegemm_plan"""
     _fields_ = [("waves", ctypes.c_int32), ("row_words", ctypes.c_int32), ("k_splits", ctypes.c_int32),
-                ("batch_group", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4)]
+                ("batch_group", ctypes.c_int32), ("psum_dtype", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
 
     @classmethod
-    def make(cls, waves: int, row_words: int, k_splits: int, batch_group: int = 1):
-        return cls(waves, row_words, k_splits, batch_group, (ctypes.c_int32 * 4)(0, 0, 0, 0))
+    def make(cls, waves: int, row_words: int, k_splits: int, batch_group: int = 1, psum_dtype: int = 0):
+        return cls(waves, row_words, k_splits, batch_group, psum_dtype, (ctypes.c_int32 * 3)(0, 0, 0))
 
     def __repr__(self):
+        tail = ", psum_dtype=fp16" if self.psum_dtype == PSUM_FP16 else ""
         return (f"Plan(waves={self.waves}, row_words={self.row_words}, k_splits={self.k_splits}, "
-                f"batch_group={self.batch_group})")
+                f"batch_group={self.batch_group}{tail})")
 
 
 def lib_path() -> str:

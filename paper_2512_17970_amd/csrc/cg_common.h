@@ -55,6 +55,7 @@ struct Geometry {
     int GPU;        // scale groups per 32-sub-vector unit: max(1, 32 * v / g); 0 when g = -1
     int gshift;     // a lane's group inside its unit = (sub-vector index in the unit) >> gshift
     bool y_fp32;
+    bool psum_fp16;  // Psumbook stored as fp16 pairs (plan field psum_dtype)
 };
 
 __host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }

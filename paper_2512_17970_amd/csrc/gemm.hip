@@ -115,6 +115,15 @@ static int gemm_launch(const codegemm_desc* desc, const codegemm_plan* plan, con
         }
         return CODEGEMM_UNSUPPORTED;
     }
+    if (g.psum_fp16) {
+        switch (g.m) {
+            case 1: return g.g > 0 ? launch_gemm_h_gs_m1(g, p, s) : launch_gemm_h_m1(g, p, s);
+            case 2: return g.g > 0 ? launch_gemm_h_gs_m2(g, p, s) : launch_gemm_h_m2(g, p, s);
+            case 3: return g.g > 0 ? launch_gemm_h_gs_m3(g, p, s) : launch_gemm_h_m3(g, p, s);
+            case 4: return g.g > 0 ? launch_gemm_h_gs_m4(g, p, s) : launch_gemm_h_m4(g, p, s);
+        }
+        return CODEGEMM_UNSUPPORTED;
+    }
     if (g.g > 0) {
         switch (g.m) {
             case 1: return launch_gemm_gs_m1(g, p, s);

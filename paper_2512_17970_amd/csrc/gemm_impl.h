@@ -126,6 +126,81 @@ __device__ __forceinline__ void mfma_block_to_lds(float* buf, int c, int iblk, i
             *reinterpret_cast<lds_float*>(static_cast<uintptr_t>(dst + (uint32_t)(8 * blk + e) * 256u)) = d[4 * blk + e];
 }
 
+// The fp16 Psumbook (plan field psum_dtype = 1): an entry is the pair of partial sums of one
+// centroid index and slot for the two codebooks of a superplane, rounded to nearest-even
+// fp16 and packed into one 32-bit word: codebook 2*sp in the low half, 2*sp + 1 in the
+// high half.  A row is still 256 bytes per centroid index, now holding the 32 slots of both
+// buffers (buffer parity at byte offset 128), so the byte address is
+//     (superplane << 16) | (code << 8) | (128 * parity + 4 * slot + 2 * (c % 2)),
+// again one byte-permute, and the bank of a lookup is again the slot.  The table of a unit is
+// half the bytes: half the LDS writes per unit, and every format double-buffers in at most 128 KB.
+template <int M>
+struct PsumLayoutH {
+    static constexpr int kSuperplanes = (M + 1) / 2;
+    static constexpr int kBytes = kSuperplanes * 65536;                 // both buffers
+};
+
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
+typedef __attribute__((address_space(3))) uint16_t lds_u16;
+
+// The 32x32 blocks (centroids 32*iblk..+31, all slots) of the two codebooks of superplane sp,
+// packed and written for accumulator groups blk_lo..blk_hi-1 (4 groups of 8 centroid rows).
+template <int M, int V>
+__device__ __forceinline__ void mfma_pair_to_lds(float* planes, int sp, int iblk, int lane, int par, int blk_lo, int blk_hi,
+                                                 typename Frag<V>::type c0, typename Frag<V>::type c1,
+                                                 typename Frag<V>::type xfrag)
+{
+    float16_t d0 = {0}, d1 = {0};
+    if constexpr (V == 16) {
+        d0 = __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_shufflevector(c0, c0, 0, 1, 2, 3),
+                                                  __builtin_shufflevector(xfrag, xfrag, 0, 1, 2, 3), d0, 0, 0, 0);
+        d0 = __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_shufflevector(c0, c0, 4, 5, 6, 7),
+                                                  __builtin_shufflevector(xfrag, xfrag, 4, 5, 6, 7), d0, 0, 0, 0);
+        d1 = __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_shufflevector(c1, c1, 0, 1, 2, 3),
+                                                  __builtin_shufflevector(xfrag, xfrag, 0, 1, 2, 3), d1, 0, 0, 0);
+        d1 = __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_shufflevector(c1, c1, 4, 5, 6, 7),
+                                                  __builtin_shufflevector(xfrag, xfrag, 4, 5, 6, 7), d1, 0, 0, 0);
+    } else {
+        d0 = __builtin_amdgcn_mfma_f32_32x32x8f16(c0, xfrag, d0, 0, 0, 0);
+        d1 = __builtin_amdgcn_mfma_f32_32x32x8f16(c1, xfrag, d1, 0, 0, 0);
+    }
+    uint32_t dst = (uint32_t)reinterpret_cast<uintptr_t>((lds_float*)planes) +
+                   (uint32_t)(sp * 65536 + par * 128 + ((iblk * 32 + 4 * (lane >> 5)) * 64 + (lane & 31)) * 4);
+    asm volatile("" : "+v"(dst));
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+        if (blk < blk_lo || blk >= blk_hi) continue;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const half2_t pr = {(_Float16)d0[4 * blk + e], (_Float16)d1[4 * blk + e]};
+            *reinterpret_cast<lds_u32*>(static_cast<uintptr_t>(dst + (uint32_t)(8 * blk + e) * 256u)) = __builtin_bit_cast(uint32_t, pr);
+        }
+    }
+}
+
+// fp16 Psum lookup: same address assembly as psum_at; a 16-bit read (the bits land in the
+// low half of the register, the high half is zero).
+template <int k>
+__device__ __forceinline__ uint32_t psum_h_at(uint32_t word, uint32_t off)
+{
+    const uint32_t addr = __builtin_amdgcn_perm(word, off, 0x0c020000u | ((4u + k) << 8));
+    return *reinterpret_cast<const lds_u16*>(static_cast<uintptr_t>(addr));
+}
+
+// acc + psum (or acc + scale * psum) for an fp16 psum: one mixed-precision fused multiply-add
+// that widens the fp16 operand exactly, so the vector-instruction count per lookup stays at
+// two (address, accumulate) as with the fp32 table.
+template <bool GS>
+__device__ __forceinline__ float accumulate_h(float acc, uint32_t hbits, _Float16 scale)
+{
+    if constexpr (GS) {
+        return __builtin_fmaf((float)scale, (float)__builtin_bit_cast(_Float16, (uint16_t)hbits), acc);
+    } else {
+        asm("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel_hi:[1,0,0]" : "+v"(acc) : "v"(hbits));
+        return acc;
+    }
+}
+
 // Psum lookup: the LDS byte address gets byte 0 from the low byte of `off`
 // (sub-offset + 4*slot), byte 1 from code byte `k` of `word`, byte 2 from byte 2 of
 // `off` (buffer and superplane), byte 3 zero; the read is a plain ds_read_b32 at that
@@ -321,20 +396,28 @@ __device__ __forceinline__ float accumulate(float acc, float psum, _Float16 scal
     else return acc + psum;
 }
 
-template <int M, int V, int NW, int RPL, int BG, int D, bool GS>
+template <int M, int V, int NW, int RPL, int BG, int D, bool GS, bool PH = false>
 __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
 {
     constexpr int NTILES = 8 * M;                      // 32x32 MFMA blocks in one Psumbook
-    constexpr int TPW = (NTILES + NW - 1) / NW;        // blocks per wavefront
+    constexpr int TPW = PH ? 1 : (NTILES + NW - 1) / NW;   // blocks per wavefront (fp32 Psumbook)
     constexpr int GPW = RPL * NW / 8;                  // 128-row granules per workgroup
     typedef PsumLayout<M> L;
-    constexpr int NBUF = L::kBuffers;
+    typedef PsumLayoutH<M> LH;
+    constexpr int NBUF = PH ? 2 : L::kBuffers;
+    // fp16 Psumbook: block pairs (superplane, 32 centroids), each built by one wavefront, or by
+    // two (each writing half of the rows) when there are more wavefronts than pairs
+    constexpr int NPAIR = 8 * LH::kSuperplanes;
+    constexpr int PPW = NPAIR >= NW ? NPAIR / NW : 1;
+    constexpr int WPP = NPAIR >= NW ? 1 : NW / NPAIR;  // wavefronts per pair (1 or 2)
+    static_assert(!PH || (NPAIR % NW == 0 || NW % NPAIR == 0), "pairs and wavefronts divide");
+    static_assert(!PH || WPP <= 2, "at most two wavefronts per pair");
     static_assert(NW == 8 || NW == 16, "8 or 16 wavefronts");
     static_assert((D & 1) == 0, "ring depth must be even (buffer parity is compile-time)");
 
     extern __shared__ __align__(16) unsigned char smem[];
     float* planes = reinterpret_cast<float*>(smem);                     // NBUF buffers of L::kBytes
-    uint32_t* flag = reinterpret_cast<uint32_t*>(smem + NBUF * L::kBytes);
+    uint32_t* flag = reinterpret_cast<uint32_t*>(smem + (PH ? LH::kBytes : NBUF * L::kBytes));
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -361,11 +444,26 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
     //
     // Centroid operands of this wavefront's MFMA blocks: fixed for the whole kernel.
     frag_t cfrag[TPW];
+    frag_t cpair[PH ? PPW : 1][2];                     // fp16 Psumbook: both codebooks of this wavefront's pairs
+    if constexpr (!PH) {
 #pragma unroll
-    for (int i = 0; i < TPW; ++i) {
-        int tile = wave + i * NW;                      // c*8 + iblk
-        if (tile >= NTILES) tile = NTILES - 1;
-        cfrag[i] = *reinterpret_cast<const frag_t*>(p.codebooks + (size_t)(tile * 32 + (lane & 31)) * V + (kvalid ? FE * khalf : 0));
+        for (int i = 0; i < TPW; ++i) {
+            int tile = wave + i * NW;                      // c*8 + iblk
+            if (tile >= NTILES) tile = NTILES - 1;
+            cfrag[i] = *reinterpret_cast<const frag_t*>(p.codebooks + (size_t)(tile * 32 + (lane & 31)) * V + (kvalid ? FE * khalf : 0));
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < PPW; ++i) {
+            const int pair = (WPP == 1) ? wave + i * NW : wave % NPAIR;        // sp*8 + iblk
+            const int sp = pair / 8, iblk = pair % 8;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int c = min(2 * sp + h, M - 1);
+                cpair[i][h] = *reinterpret_cast<const frag_t*>(p.codebooks + (size_t)((c * 8 + iblk) * 32 + (lane & 31)) * V + (kvalid ? FE * khalf : 0));
+                if (!kvalid || 2 * sp + h >= M) cpair[i][h] = zero4;           // an odd m leaves the last high half zero
+            }
+        }
     }
     // Activation operand: sub-vector (32*kt + l%32), elements 4*(l/32)..+3 (Step 1), read
     // through a descriptor that covers exactly this workgroup's K range of batch row bb.
@@ -442,17 +540,27 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
 #if CODEGEMM_ABLATE & 4
     bool first_build = true;
 #endif
-    auto build = [&](float* buf, frag_t xf) {
+    auto build = [&](float* buf, int par, frag_t xf) {
 #if CODEGEMM_ABLATE & 4
         // ablation build: only the first Psumbook is built; the activations are still consumed
         if (!first_build) { asm volatile("" :: "v"(xf)); return; }
         first_build = false;
 #endif
+        if constexpr (PH) {
 #pragma unroll
-        for (int i = 0; i < TPW; ++i) {
-            const int tile = wave + i * NW;
-            if (NTILES % NW == 0 || tile < NTILES)
-                mfma_block_to_lds<M, V>(buf, tile / 8, tile % 8, lane, kvalid ? cfrag[i] : zero4, xf);
+            for (int i = 0; i < PPW; ++i) {
+                const int pair = (WPP == 1) ? wave + i * NW : wave % NPAIR;
+                const int half = (WPP == 1) ? 0 : wave / NPAIR;
+                mfma_pair_to_lds<M, V>(planes, pair / 8, pair % 8, lane, par, WPP == 1 ? 0 : 2 * half, WPP == 1 ? 4 : 2 * half + 2,
+                                       cpair[i][0], cpair[i][1], kvalid ? xf : zero4);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+                const int tile = wave + i * NW;
+                if (NTILES % NW == 0 || tile < NTILES)
+                    mfma_block_to_lds<M, V>(buf, tile / 8, tile % 8, lane, kvalid ? cfrag[i] : zero4, xf);
+            }
         }
     };
 
@@ -495,7 +603,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
 
     // Psumbook of (unit 0, batch row 0).
     CG_STAMP(2);
-    build(planes, xr[0][0]);
+    build(planes, 0, xr[0][0]);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int d = 1; d < D; ++d) load_codes(w[d], d);
@@ -514,7 +622,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
 #pragma unroll
             for (int bb = 0; bb < BG; ++bb) {
                 const int par = (NBUF == 2) ? ((BG == 1) ? (d & 1) : (bb & 1)) : 0;   // buffer of the current Psumbook
-                float* nxt = planes + (NBUF == 2 ? (par ^ 1) : 0) * (L::kBytes / 4);
+                float* nxt = planes + ((NBUF == 2 && !PH) ? (par ^ 1) : 0) * (L::kBytes / 4);   // fp32 Psumbook: the other buffer
                 const bool last_bb = (bb == BG - 1);
                 const bool has_next = !last_bb || u + 1 < nq;
                 // gather the current one (Step 3)
@@ -527,8 +635,9 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
                         for (int i = 0; i < 2 * M; ++i) asm volatile("" : "+v"(w[d][q][i]));
 #pragma unroll
                         for (int c = 0; c < M; ++c) {
-                            const uint32_t off = slot4 + (uint32_t)L::sub_bytes(c) +
-                                                 ((uint32_t)(L::superplane(c) + par * L::kSuperplanes) << 16);
+                            const uint32_t off = PH ? slot4 + (uint32_t)(2 * (c % 2) + 128 * par) + ((uint32_t)(c / 2) << 16)
+                                                    : slot4 + (uint32_t)L::sub_bytes(c) +
+                                                          ((uint32_t)(L::superplane(c) + par * L::kSuperplanes) << 16);
                             const uint32_t lo = w[d][q][2 * c], hi = w[d][q][2 * c + 1];
                             const half8_t sv = sc[GS ? d % DS : 0][q];
 #if CODEGEMM_ABLATE & 2
@@ -547,14 +656,14 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
                             (void)sv;
                             continue;
 #endif
-                            acc[bb][q][0] = accumulate<GS>(acc[bb][q][0], psum_at<0>(lo, off), sv[0]);
-                            acc[bb][q][1] = accumulate<GS>(acc[bb][q][1], psum_at<1>(lo, off), sv[1]);
-                            acc[bb][q][2] = accumulate<GS>(acc[bb][q][2], psum_at<2>(lo, off), sv[2]);
-                            acc[bb][q][3] = accumulate<GS>(acc[bb][q][3], psum_at<3>(lo, off), sv[3]);
-                            acc[bb][q][4] = accumulate<GS>(acc[bb][q][4], psum_at<0>(hi, off), sv[4]);
-                            acc[bb][q][5] = accumulate<GS>(acc[bb][q][5], psum_at<1>(hi, off), sv[5]);
-                            acc[bb][q][6] = accumulate<GS>(acc[bb][q][6], psum_at<2>(hi, off), sv[6]);
-                            acc[bb][q][7] = accumulate<GS>(acc[bb][q][7], psum_at<3>(hi, off), sv[7]);
+                            acc[bb][q][0] = PH ? accumulate_h<GS>(acc[bb][q][0], psum_h_at<0>(lo, off), sv[0]) : accumulate<GS>(acc[bb][q][0], psum_at<0>(lo, off), sv[0]);
+                            acc[bb][q][1] = PH ? accumulate_h<GS>(acc[bb][q][1], psum_h_at<1>(lo, off), sv[1]) : accumulate<GS>(acc[bb][q][1], psum_at<1>(lo, off), sv[1]);
+                            acc[bb][q][2] = PH ? accumulate_h<GS>(acc[bb][q][2], psum_h_at<2>(lo, off), sv[2]) : accumulate<GS>(acc[bb][q][2], psum_at<2>(lo, off), sv[2]);
+                            acc[bb][q][3] = PH ? accumulate_h<GS>(acc[bb][q][3], psum_h_at<3>(lo, off), sv[3]) : accumulate<GS>(acc[bb][q][3], psum_at<3>(lo, off), sv[3]);
+                            acc[bb][q][4] = PH ? accumulate_h<GS>(acc[bb][q][4], psum_h_at<0>(hi, off), sv[4]) : accumulate<GS>(acc[bb][q][4], psum_at<0>(hi, off), sv[4]);
+                            acc[bb][q][5] = PH ? accumulate_h<GS>(acc[bb][q][5], psum_h_at<1>(hi, off), sv[5]) : accumulate<GS>(acc[bb][q][5], psum_at<1>(hi, off), sv[5]);
+                            acc[bb][q][6] = PH ? accumulate_h<GS>(acc[bb][q][6], psum_h_at<2>(hi, off), sv[6]) : accumulate<GS>(acc[bb][q][6], psum_at<2>(hi, off), sv[6]);
+                            acc[bb][q][7] = PH ? accumulate_h<GS>(acc[bb][q][7], psum_h_at<3>(hi, off), sv[7]) : accumulate<GS>(acc[bb][q][7], psum_at<3>(hi, off), sv[7]);
                         }
                     }
                 }
@@ -562,8 +671,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
                     // build the next Psumbook of the sequence into the other buffer (after the
                     // gather in program order: the LDS reads that feed the accumulators go first)
                     if (has_next) {
-                        if (last_bb) build(nxt, xr[(d + 1) % D][0]);
-                        else build(nxt, xr[d][(bb + 1) % BG]);
+                        if (last_bb) build(nxt, par ^ 1, xr[(d + 1) % D][0]);
+                        else build(nxt, par ^ 1, xr[d][(bb + 1) % BG]);
                     }
                     if (BG == 1) xr[(d + 1) % D][0] = load_x(u + 1 + D, 0);   // its slot is free again
                 }
@@ -571,8 +680,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
                     // single buffer: everyone must be done reading before it is rebuilt
                     __syncthreads();
                     if (has_next) {
-                        if (last_bb) build(nxt, xr[(d + 1) % D][0]);
-                        else build(nxt, xr[d][(bb + 1) % BG]);
+                        if (last_bb) build(nxt, par ^ 1, xr[(d + 1) % D][0]);
+                        else build(nxt, par ^ 1, xr[d][(bb + 1) % BG]);
                     }
                     if (BG == 1) xr[(d + 1) % D][0] = load_x(u + 1 + D, 0);
                 }
@@ -620,12 +729,12 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
 
 int set_max_lds(const void* fn, size_t bytes);
 
-template <int M, int V, int NW, int RPL, int BG, int D, bool GS>
+template <int M, int V, int NW, int RPL, int BG, int D, bool GS, bool PH = false>
 int launch_gemm_one(const Geometry& g, const GemmParams& p, hipStream_t stream)
 {
-    auto fn = gemm_kernel<M, V, NW, RPL, BG, D, GS>;
+    auto fn = gemm_kernel<M, V, NW, RPL, BG, D, GS, PH>;
     typedef PsumLayout<M> L;
-    const size_t lds = (size_t)L::kBuffers * L::kBytes + 64;
+    const size_t lds = (PH ? (size_t)PsumLayoutH<M>::kBytes : (size_t)L::kBuffers * L::kBytes) + 64;
     int st = set_max_lds(reinterpret_cast<const void*>(fn), lds);
     if (st != CODEGEMM_OK) return st;
     const dim3 grid((unsigned)g.NKS, (unsigned)g.NBLK, (unsigned)g.NG);
@@ -654,6 +763,28 @@ int launch_gemm_mvb(const Geometry& g, const GemmParams& p, hipStream_t stream)
         if (g.NW == 16 && g.RPL == 4) return launch_gemm_one<M, V, 16, 4, BG, 2, GS>(g, p, stream);
     }
     return CODEGEMM_UNSUPPORTED;
+}
+
+// fp16 Psumbook (batch rows one at a time): the same block shapes.
+template <int M, int V, bool GS>
+int launch_gemm_h_mv(const Geometry& g, const GemmParams& p, hipStream_t stream)
+{
+    if (g.NW == 8 && g.RPL == 1) return launch_gemm_one<M, V, 8, 1, 1, 2, GS, true>(g, p, stream);
+    if (g.NW == 16 && g.RPL == 1) return launch_gemm_one<M, V, 16, 1, 1, 2, GS, true>(g, p, stream);
+    if (g.NW == 8 && g.RPL == 2) return launch_gemm_one<M, V, 8, 2, 1, 2, GS, true>(g, p, stream);
+    if constexpr (!GS) {   // with group scales the 16-wavefront, 2-row-word shape runs out of registers
+        if (g.NW == 16 && g.RPL == 2) return launch_gemm_one<M, V, 16, 2, 1, 2, GS, true>(g, p, stream);
+    }
+    return CODEGEMM_UNSUPPORTED;
+}
+
+template <int M, bool GS>
+int launch_gemm_h_m(const Geometry& g, const GemmParams& p, hipStream_t stream)
+{
+    if (g.BG != 1) return CODEGEMM_UNSUPPORTED;
+    if (g.v == 16) return launch_gemm_h_mv<M, 16, GS>(g, p, stream);
+    if (g.v == 8) return launch_gemm_h_mv<M, 8, GS>(g, p, stream);
+    return launch_gemm_h_mv<M, 4, GS>(g, p, stream);
 }
 
 template <int M, bool GS>
@@ -686,5 +817,13 @@ int launch_gemm_gs_m1(const Geometry& g, const GemmParams& p, hipStream_t stream
 int launch_gemm_gs_m2(const Geometry& g, const GemmParams& p, hipStream_t stream);
 int launch_gemm_gs_m3(const Geometry& g, const GemmParams& p, hipStream_t stream);
 int launch_gemm_gs_m4(const Geometry& g, const GemmParams& p, hipStream_t stream);
+int launch_gemm_h_m1(const Geometry& g, const GemmParams& p, hipStream_t stream);      // fp16 Psumbook
+int launch_gemm_h_m2(const Geometry& g, const GemmParams& p, hipStream_t stream);
+int launch_gemm_h_m3(const Geometry& g, const GemmParams& p, hipStream_t stream);
+int launch_gemm_h_m4(const Geometry& g, const GemmParams& p, hipStream_t stream);
+int launch_gemm_h_gs_m1(const Geometry& g, const GemmParams& p, hipStream_t stream);   // fp16 Psumbook, group scales
+int launch_gemm_h_gs_m2(const Geometry& g, const GemmParams& p, hipStream_t stream);
+int launch_gemm_h_gs_m3(const Geometry& g, const GemmParams& p, hipStream_t stream);
+int launch_gemm_h_gs_m4(const Geometry& g, const GemmParams& p, hipStream_t stream);
 
 }  // namespace cg

@@ -33,8 +33,14 @@ static int validate_plan(const codegemm_desc* d, const codegemm_plan* p)
     if (p->row_words == 4 && p->waves != 16 && p->batch_group != 4) return CODEGEMM_UNSUPPORTED;
     if (p->k_splits < 1) return CODEGEMM_UNSUPPORTED;
     if (p->batch_group != 1 && p->batch_group != 2 && p->batch_group != 4) return CODEGEMM_UNSUPPORTED;
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 3; ++i)
         if (p->reserved[i]) return CODEGEMM_INVALID_ARG;
+    if (p->psum_dtype != CODEGEMM_PSUM_FP32 && p->psum_dtype != CODEGEMM_PSUM_FP16) return CODEGEMM_UNSUPPORTED;
+    if (p->psum_dtype == CODEGEMM_PSUM_FP16) {
+        if (p->batch_group != 1 || p->row_words > 2) return CODEGEMM_UNSUPPORTED;
+        if (d->group_size > 0 && p->waves == 16 && p->row_words == 2) return CODEGEMM_UNSUPPORTED;   // registers
+        return CODEGEMM_OK;
+    }
     const int m = d->num_codebooks;
     if (p->batch_group == 4) {
         // the batched kernel: 32 accumulators per row word
@@ -137,6 +143,7 @@ int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g
     g->NW = plan->waves;
     g->RPL = plan->row_words;
     g->BG = plan->batch_group;
+    g->psum_fp16 = plan->psum_dtype == CODEGEMM_PSUM_FP16;
     g->NGR = ceil_div(g->N, kGranuleRows);
     g->NBLK = ceil_div(g->NGR, g->RPL * g->NW / (g->BG == 4 ? 4 : 8));
     g->NKT = ceil_div(g->J, kSlots);

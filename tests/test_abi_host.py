@@ -164,6 +164,25 @@ def test_invalid_plans_are_rejected():
     assert cg.codegemm_workspace_bytes(d3, cg.Plan.make(16, 2, 1, 2)) == 0    # 2 rows x 3 codebooks x 16 rows per lane
 
 
+def test_fp16_psumbook_plans():
+    """psum_dtype = 1 needs batch rows one at a time and at most two row words; with group scales the
+    16-wavefront two-row-word shape is not offered; the default plan never picks it."""
+    d = cg.Desc.make(1, 4096, 4096, 8, 3)
+    fp16 = binding.PSUM_FP16
+    for p in (cg.Plan.make(8, 1, 2, 1, fp16), cg.Plan.make(16, 2, 4, 1, fp16), cg.Plan.make(8, 2, 1, 1, fp16)):
+        assert cg.codegemm_workspace_bytes(d, p) > 0
+    for p in (cg.Plan.make(16, 2, 4, 2, fp16), cg.Plan.make(16, 1, 4, 4, fp16), cg.Plan.make(16, 4, 4, 1, fp16), cg.Plan.make(8, 1, 2, 1, 2)):
+        assert cg.codegemm_workspace_bytes(d, p) == 0
+    dg = cg.Desc.make(1, 4096, 4096, 8, 2, g=128)
+    assert cg.codegemm_workspace_bytes(dg, cg.Plan.make(16, 2, 4, 1, fp16)) == 0
+    assert cg.codegemm_workspace_bytes(dg, cg.Plan.make(16, 1, 4, 1, fp16)) > 0
+    assert cg.codegemm_workspace_bytes(dg, cg.Plan.make(8, 2, 4, 1, fp16)) > 0
+    import synth
+    for cases in synth.workloads().values():
+        for c in cases:
+            assert cg.codegemm_default_plan(cg.Desc.make(c.B, c.K, c.N, c.v, c.m, g=c.g)).psum_dtype == 0
+
+
 def test_compressed_bytes_closed_form():
     # 8192 -> 28672, v8 m2, batch 1: codes 58,720,256 + codebooks 8192 + scales 57344 + x 16384 + y 57344
     assert cg.compressed_bytes(1, 8192, 28672, 8, 2) == 58720256 + 8192 + 57344 + 16384 + 57344

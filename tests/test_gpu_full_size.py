@@ -75,3 +75,27 @@ def test_skewed_codes_at_70b_shape():
     y = layer.gemm()
     torch.cuda.synchronize()
     check_against_oracle(y.cpu().numpy(), y_ref, T, "skewed codes")
+
+
+@pytest.mark.parametrize("name", ["c3_8192x8192_v8m2_b1", "c3_8192x1024_v8m2_b1", "c3_8192x28672_v8m2_b1", "c3_28672x8192_v8m2_b1",
+                                  "c5_8192x28672_v8m3_b1", "c2_4096x14336_v4m1_b1", "c8_8192x28672_v8m2g128_b1"])
+def test_fp16_psumbook_at_full_size(name):
+    """The fp16 Psumbook option at the graded shapes, with the default block shape: the acceptance bar, and
+    relative L2 below 6e-4 (fp16 rounding of the partial sums and of y together predict about 4e-4)."""
+    case = synth.find_case(name)
+    inp = synth.generate(case)
+    y_ref, T = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+    d = cg.Desc.make(case.B, case.K, case.N, case.v, case.m, g=case.g)
+    p = cg.codegemm_default_plan(d)
+    rw = 1 if (case.g > 0 and p.waves == 16) else p.row_words
+    plan = cg.Plan.make(p.waves, rw, p.k_splits, 1, cg.binding.PSUM_FP16)
+    layer = DeviceLayer(inp, plan=plan)
+    print(f"[fp16 psumbook] {case.name} {layer.plan}", flush=True)
+    y = layer.gemm()
+    torch.cuda.synchronize()
+    rel = check_against_oracle(y.cpu().numpy(), y_ref, T, f"fp16 Psumbook {case.name}")
+    print(f"[fp16 psumbook] relative L2 {rel:.2e}", flush=True)
+    assert rel < 6e-4
+    y2 = layer.gemm()
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)

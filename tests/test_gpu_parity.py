@@ -130,6 +130,43 @@ def test_group_scales_every_plan_shape(v, m, g, k_splits, waves, row_words, bg):
     run_case(case, plan=cg.Plan.make(waves, row_words, k_splits, bg), dequant=False)
 
 
+def fp16_plan_ok(waves, row_words, g):
+    return not (g > 0 and waves == 16 and row_words == 2)
+
+
+@pytest.mark.parametrize("waves,row_words", [(8, 1), (16, 1), (8, 2), (16, 2)])
+@pytest.mark.parametrize("k_splits", [1, 3])
+@pytest.mark.parametrize("v,m,g", [(8, 2, -1), (4, 1, -1), (8, 1, -1), (8, 3, -1), (4, 4, -1), (16, 4, -1), (16, 3, -1), (4, 2, -1),
+                                   (8, 2, 128), (8, 2, 8), (4, 1, 32), (8, 3, 64), (16, 2, 256)])
+def test_fp16_psumbook_every_plan_shape(v, m, g, k_splits, waves, row_words):
+    """The Psumbook stored as fp16 pairs (plan field psum_dtype = 1): every partial sum carries one more
+    rounding of relative size 2^-11, which the acceptance bar (relative L2 <= 1e-3, per element
+    <= 1e-2 sum|terms|) has room for; checked at that bar, on ragged shapes, for every block shape."""
+    if not fp16_plan_ok(waves, row_words, g):
+        pytest.skip("plan not offered with an fp16 Psumbook and group scales")
+    case = synth.custom_case(max(g, v * 32) * 5 + (0 if g > 0 else v * 7), 1300, v, m, 1, seed=191, g=g)
+    run_case(case, plan=cg.Plan.make(waves, row_words, k_splits, 1, cg.binding.PSUM_FP16), dequant=False)
+
+
+def test_fp16_psumbook_is_exact_on_integer_partial_sums():
+    """+-1 codebook and small integer x: every partial sum is an integer below 2048, which fp16 holds
+    exactly, so the fp16 Psumbook must give the oracle's result bit for bit (fp32 output)."""
+    v, K, N = 8, 4096, 1100
+    rng = np.random.default_rng(23)
+    i = np.arange(256)[:, None]
+    case = synth.custom_case(K, N, v, 2, 1, seed=2)
+    inp = synth.generate(case)
+    inp.codebooks = np.stack([np.where((i >> np.arange(v)[None, :]) & 1, 1.0, -1.0), np.where((i >> np.arange(v)[None, :]) & 1, 2.0, 0.0)]).astype(np.float16)
+    inp.x = rng.integers(-8, 9, (1, K)).astype(np.float16)
+    inp.scales = np.ones(N, np.float16)
+    y_ref, _ = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+    for waves, rw in ((8, 2), (16, 2), (16, 1)):
+        layer = DeviceLayer(inp, plan=cg.Plan.make(waves, rw, 3, 1, cg.binding.PSUM_FP16), y_fp32=True)
+        y = layer.gemm()
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy().astype(np.float64), y_ref)
+
+
 def test_pack_scales_matches_documented_layout():
     for (K, N, v, g) in [(1024, 300, 8, 128), (1024, 300, 8, 8), (2048, 129, 8, 1024), (512, 700, 4, 4), (640, 64, 4, 128)]:
         case = synth.custom_case(K, N, v, 1, 1, seed=8, g=g)
