@@ -41,7 +41,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--repeats", type=int, default=7,
                     help="the K timed steps are run this many times; ms_per_step is the median run, min and max go to config")
-    ap.add_argument("--workload", default="c3", help="c1..c11 | a single case name from synth.workloads()")
+    ap.add_argument("--workload", default="c3", help="c1..c13 | a single case name from synth.workloads()")
     ap.add_argument("--launch", default="graph", choices=["graph", "direct"],
                     help="graph: the K timed steps are one captured HIP graph (no host launch cost); direct: plain launches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -336,7 +336,7 @@ def main():
         return
     wl = synth.workloads()
     key = args.workload.lower()
-    if key in ("c1", "c2", "c3", "c4", "c5", "c6", "c7", "c8", "c9", "c10", "c11"):
+    if key[:1] == "c" and key[1:].isdigit() and int(key[1:]) in wl:
         cases = wl[int(key[1:])]
     else:
         cases = [synth.find_case(args.workload)]

@@ -76,6 +76,14 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
         // groups to fill the chip with, 512 otherwise; K ranges are cut so that all batch
         // groups together give close to, but not more than, 256 workgroups.
         const int groups = ceil_div(batch, 4);
+        auto fill = [&](int waves, int row_words, int* k_splits) {      // workgroups of a block shape
+            const int nblk = ceil_div(ngr, waves * row_words / 4) * groups;
+            int nks = 256 / nblk;
+            if (nks > nkt) nks = nkt;
+            if (nks < 1) nks = 1;
+            *k_splits = ceil_div(nkt, ceil_div(nkt, nks));
+            return nblk * *k_splits;
+        };
         p->waves = 16;
         p->row_words = groups >= 2 ? 2 : 1;
         if (groups == 1) {
@@ -88,11 +96,28 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
             if (nks2 < 1) nks2 = 1;
             if (ceil_div(nkt, nks2) >= 4 && nks2 <= 16) p->row_words = 2;   // (28 ranges: 30.1 -> 32.7 us)
         }
-        const int nblk4 = ceil_div(ngr, 4 * p->row_words) * groups;
-        int nks4 = 256 / nblk4;
-        if (nks4 > nkt) nks4 = nkt;
-        if (nks4 < 1) nks4 = 1;
-        p->k_splits = ceil_div(nkt, ceil_div(nkt, nks4));
+        // The 1024-row shape with 16 wavefronts has 128 registers per lane: with group scales, or
+        // three and more codebooks, its 64 accumulators and the scale ring no longer fit and it
+        // spills (8192->28672, m2v8g128, batch 8: 93 us against 56 us with 512-row blocks).
+        if (p->row_words == 2 && (d->group_size > 0 || m >= 3)) p->row_words = 1;
+        // Small matrices: a shorter block when the taller one leaves most of the chip idle
+        // (2048^2 at batch 8: 32 workgroups of 1024 rows 19.5 us, 128 of 256 rows 7.8 us).
+        int ks = 1;
+        int wgs = fill(p->waves, p->row_words, &ks);
+        if (wgs < 192 && p->row_words == 2) {
+            int ks1 = 1;
+            const int w1 = fill(16, 1, &ks1);
+            if (w1 > wgs) { p->row_words = 1; wgs = w1; ks = ks1; }
+        }
+        if (wgs < 192 || ks > 32) {
+            // also when the chip is only filled by cutting K into more than 32 ranges: the last
+            // workgroup of a row block then adds that many partial sums per output
+            // (8192->2048, v4 m1, batch 4: 64 ranges 13.2 us)
+            int ks8 = 1;
+            const int w8 = fill(8, 1, &ks8);
+            if (w8 > wgs || (w8 >= 192 && ks8 < ks)) { p->waves = 8; p->row_words = 1; wgs = w8; ks = ks8; }
+        }
+        p->k_splits = ks;
         return;
     }
     // 512-row blocks for large matrices with up to three codebooks, 256-row blocks (more, shorter
