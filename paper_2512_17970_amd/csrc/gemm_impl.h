@@ -212,6 +212,78 @@ __device__ __forceinline__ float psum_at(uint32_t word, uint32_t off)
     return *reinterpret_cast<const lds_float*>(static_cast<uintptr_t>(addr));
 }
 
+// The eight Psum lookups of one code word pair (8 rows, one codebook) and their additions as
+// one instruction sequence that the compiler cannot stretch: address, read, address, read,
+// ..., then each addition as soon as its read is back (LDS reads return in order, so once at
+// most 7 - i accesses are outstanding, read i has arrived, whatever else was in flight
+// before).  Used by the block shapes whose accumulators and code ring leave few registers:
+// left to the scheduler, all reads of a unit are issued ahead of the first addition, their
+// results stay live, and those shapes spill (measured: the 16-wavefront shapes with three or
+// four codebooks, two batch rows, or 1024 rows).  The shapes that fit keep the compiler's
+// schedule, which hides the LDS latency a little better (8192->28672, m = 2: 14.3 against 14.8 us).
+#define CG_GATHER8_READS \
+        "v_perm_b32 %8, %16, %18, %19\n\t"  "ds_read_b32 %8, %8\n\t"   \
+        "v_perm_b32 %9, %16, %18, %20\n\t"  "ds_read_b32 %9, %9\n\t"   \
+        "v_perm_b32 %10, %16, %18, %21\n\t" "ds_read_b32 %10, %10\n\t" \
+        "v_perm_b32 %11, %16, %18, %22\n\t" "ds_read_b32 %11, %11\n\t" \
+        "v_perm_b32 %12, %17, %18, %19\n\t" "ds_read_b32 %12, %12\n\t" \
+        "v_perm_b32 %13, %17, %18, %20\n\t" "ds_read_b32 %13, %13\n\t" \
+        "v_perm_b32 %14, %17, %18, %21\n\t" "ds_read_b32 %14, %14\n\t" \
+        "v_perm_b32 %15, %17, %18, %22\n\t" "ds_read_b32 %15, %15\n\t"
+#define CG_GATHER8_OUT(a) "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]), \
+        "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3), "=&v"(t4), "=&v"(t5), "=&v"(t6), "=&v"(t7)
+constexpr uint32_t kSel0 = 0x0c020400u, kSel1 = 0x0c020500u, kSel2 = 0x0c020600u, kSel3 = 0x0c020700u;   // byte k of the code word into address byte 1
+
+__device__ __forceinline__ void gather8(float (&a)[8], uint32_t lo, uint32_t hi, uint32_t off)
+{
+    uint32_t t0, t1, t2, t3, t4, t5, t6, t7;
+    asm volatile(CG_GATHER8_READS
+        "s_waitcnt lgkmcnt(7)\n\t" "v_add_f32 %0, %0, %8\n\t"
+        "s_waitcnt lgkmcnt(6)\n\t" "v_add_f32 %1, %1, %9\n\t"
+        "s_waitcnt lgkmcnt(5)\n\t" "v_add_f32 %2, %2, %10\n\t"
+        "s_waitcnt lgkmcnt(4)\n\t" "v_add_f32 %3, %3, %11\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t" "v_add_f32 %4, %4, %12\n\t"
+        "s_waitcnt lgkmcnt(2)\n\t" "v_add_f32 %5, %5, %13\n\t"
+        "s_waitcnt lgkmcnt(1)\n\t" "v_add_f32 %6, %6, %14\n\t"
+        "s_waitcnt lgkmcnt(0)\n\t" "v_add_f32 %7, %7, %15"
+        : CG_GATHER8_OUT(a)
+        : "v"(lo), "v"(hi), "v"(off), "s"(kSel0), "s"(kSel1), "s"(kSel2), "s"(kSel3)
+        : "memory");
+}
+
+// The same with group scales: acc += scale[row] * psum as one mixed-precision fused
+// multiply-add that widens the fp16 scale exactly (the scales of rows 2i and 2i + 1 are the
+// low and high half of sc[i]).
+__device__ __forceinline__ void gather8_scaled(float (&a)[8], uint32_t lo, uint32_t hi, uint32_t off, const uint32_t (&sc)[4])
+{
+    uint32_t t0, t1, t2, t3, t4, t5, t6, t7;
+    asm volatile(CG_GATHER8_READS
+        "s_waitcnt lgkmcnt(7)\n\t" "v_fma_mix_f32 %0, %23, %8, %0 op_sel_hi:[1,0,0]\n\t"
+        "s_waitcnt lgkmcnt(6)\n\t" "v_fma_mix_f32 %1, %23, %9, %1 op_sel:[1,0,0] op_sel_hi:[1,0,0]\n\t"
+        "s_waitcnt lgkmcnt(5)\n\t" "v_fma_mix_f32 %2, %24, %10, %2 op_sel_hi:[1,0,0]\n\t"
+        "s_waitcnt lgkmcnt(4)\n\t" "v_fma_mix_f32 %3, %24, %11, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t" "v_fma_mix_f32 %4, %25, %12, %4 op_sel_hi:[1,0,0]\n\t"
+        "s_waitcnt lgkmcnt(2)\n\t" "v_fma_mix_f32 %5, %25, %13, %5 op_sel:[1,0,0] op_sel_hi:[1,0,0]\n\t"
+        "s_waitcnt lgkmcnt(1)\n\t" "v_fma_mix_f32 %6, %26, %14, %6 op_sel_hi:[1,0,0]\n\t"
+        "s_waitcnt lgkmcnt(0)\n\t" "v_fma_mix_f32 %7, %26, %15, %7 op_sel:[1,0,0] op_sel_hi:[1,0,0]"
+        : CG_GATHER8_OUT(a)
+        : "v"(lo), "v"(hi), "v"(off), "s"(kSel0), "s"(kSel1), "s"(kSel2), "s"(kSel3),
+          "v"(sc[0]), "v"(sc[1]), "v"(sc[2]), "v"(sc[3])
+        : "memory");
+}
+#undef CG_GATHER8_READS
+#undef CG_GATHER8_OUT
+
+// Whether a block shape of the batch-1 kernel takes the fixed gather sequence above: the shapes
+// that otherwise spill registers (128 per lane with 16 wavefronts, 256 with 8).
+template <int M, int V, int NW, int RPL, int BG, bool GS>
+__host__ __device__ constexpr bool fixed_gather()
+{
+    const int words = RPL * BG * M;                        // 8-accumulator groups times code words per unit
+    if (NW == 8) return words >= 16;
+    return words >= 8 || (V == 16 && M == 3 && RPL * BG == 2) || (GS && BG == 2 && RPL == 2);
+}
+
 // v + (v moved across lanes by a DPP control).  Lanes the control does not write add 0.
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ float dpp_add(float v)
@@ -640,6 +712,18 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
                                                           ((uint32_t)(L::superplane(c) + par * L::kSuperplanes) << 16);
                             const uint32_t lo = w[d][q][2 * c], hi = w[d][q][2 * c + 1];
                             const half8_t sv = sc[GS ? d % DS : 0][q];
+#if !CODEGEMM_ABLATE
+                            if constexpr (!PH && fixed_gather<M, V, NW, RPL, BG, GS>()) {
+                                if constexpr (GS) {
+                                    const u32x4_t sw = __builtin_bit_cast(u32x4_t, sv);
+                                    const uint32_t s4[4] = {sw.x, sw.y, sw.z, sw.w};
+                                    gather8_scaled(acc[bb][q], lo, hi, off, s4);
+                                } else {
+                                    gather8(acc[bb][q], lo, hi, off);
+                                }
+                                continue;
+                            }
+#endif
 #if CODEGEMM_ABLATE & 2
                             // ablation build: the code words are consumed, nothing is gathered
                             acc[bb][q][c & 7] += __builtin_bit_cast(float, (lo ^ hi) & 0x007fffffu);

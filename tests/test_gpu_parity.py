@@ -118,7 +118,7 @@ def test_group_scales_default_plan(K, N, v, m, B, g):
     run_case(synth.custom_case(K, N, v, m, B, seed=5150 + K + N + g, g=g))
 
 
-@pytest.mark.parametrize("waves,row_words,bg", [(8, 1, 1), (16, 1, 1), (8, 2, 1), (16, 2, 1), (8, 2, 2), (16, 1, 2),
+@pytest.mark.parametrize("waves,row_words,bg", [(8, 1, 1), (16, 1, 1), (8, 2, 1), (16, 2, 1), (8, 2, 2), (16, 1, 2), (16, 2, 2),
                                                 (16, 1, 4), (8, 1, 4), (8, 2, 4), (16, 2, 4), (8, 4, 4)])
 @pytest.mark.parametrize("k_splits", [1, 3])
 @pytest.mark.parametrize("v,m,g", [(8, 2, 128), (8, 2, 8), (4, 1, 32), (8, 3, 64), (4, 4, 16), (8, 1, 512)])
