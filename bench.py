@@ -53,6 +53,9 @@ def parse():
                     help="time every launch plan shape x K-split count for every shape of the workload (cold)")
     ap.add_argument("--psumbook", action="store_true",
                     help="instead of the GEMM: time the stand-alone Psumbook build (vector ALU and MFMA) at batch 1, 8, 32")
+    ap.add_argument("--memcpy", action="store_true",
+                    help="instead of the GEMM: time the runtime's device-to-device copy at the code sizes of the 70B shapes and at "
+                         "1 GiB (reads and writes that many bytes each): what this machine's memory system gives a plain kernel")
     ap.add_argument("--ablate", type=int, default=0,
                     help="time an ablation build of the library instead (libcodegemm_ablate_<mask>.so; outputs are wrong on "
                          "purpose): 2 no gather, 4 no Psumbook build after the first, 8 no exchange between workgroups; "
@@ -247,6 +250,48 @@ def psumbook_bench(torch, cg, synth):
                     f"{P.numel() * 4 / us * 1e-3:.0f} GB/s written, {2 * macs / us * 1e-6:.2f} TFLOP/s")
 
 
+def memcpy_report(torch):
+    """Device-to-device copies through the runtime's own copy kernel, back to back in one HIP graph, rotating over a
+    2 GiB pool so that nothing is served from the caches: us per copy and GB/s counting bytes read + bytes written."""
+    pool = torch.empty(2 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    rows = []
+    for nbytes in (16777216, 58720256, 1 << 30):
+        half = pool.numel() // 2
+        slots = max(1, half // nbytes)
+        n = 100 if nbytes < (1 << 28) else 4
+        state = {"i": 0}
+
+        def copy():
+            k = state["i"] % slots
+            state["i"] += 1
+            pool[half + k * nbytes: half + (k + 1) * nbytes].copy_(pool[k * nbytes:(k + 1) * nbytes])
+
+        for _ in range(3):
+            copy()
+        g = graph_of(torch, copy, n)
+        g.replay()
+        us = statistics.median(time_region(torch, g.replay, 1) for _ in range(5)) * 1e3 / n
+        row = {"bytes": nbytes, "us_per_copy": us, "GBps_read_plus_write": 2 * nbytes / us * 1e-3}
+        log(f"  copy of {nbytes} bytes: {us:.2f} us, {2 * nbytes / us * 1e-3:.0f} GB/s (read + write)")
+        # read-only reference: torch's reduction kernel over the same bytes (reads nbytes, writes a scalar)
+        words = pool.view(torch.int64)
+        out = torch.zeros((), dtype=torch.int64, device="cuda")
+        state["i"] = 0
+
+        def reduce():
+            k = state["i"] % (2 * slots)
+            state["i"] += 1
+            torch.sum(words[k * nbytes // 8:(k + 1) * nbytes // 8], dim=0, out=out)
+
+        for _ in range(3):
+            reduce()
+        us_r = statistics.median(time_region(torch, reduce, n) for _ in range(5)) * 1e3 / n
+        row.update({"us_per_read_only_reduction": us_r, "GBps_read_only": nbytes / us_r * 1e-3})
+        log(f"  read-only reduction (torch.sum) of {nbytes} bytes: {us_r:.2f} us, {nbytes / us_r * 1e-3:.0f} GB/s")
+        rows.append(row)
+    print(json.dumps({"memcpy": rows}))
+
+
 def phases_report(torch, cg, layers):
     """Where the time of one call goes, per shape: clock stamps of the workgroups (diagnostic build)."""
     from paper_2512_17970_amd import phases
@@ -333,6 +378,9 @@ def main():
     cg.load()
     if args.psumbook:
         psumbook_bench(torch, cg, synth)
+        return
+    if args.memcpy:
+        memcpy_report(torch)
         return
     wl = synth.workloads()
     key = args.workload.lower()
