@@ -289,7 +289,17 @@ def memcpy_report(torch):
         row.update({"us_per_read_only_reduction": us_r, "GBps_read_only": nbytes / us_r * 1e-3})
         log(f"  read-only reduction (torch.sum) of {nbytes} bytes: {us_r:.2f} us, {nbytes / us_r * 1e-3:.0f} GB/s")
         rows.append(row)
-    print(json.dumps({"memcpy": rows}))
+    # the floor of a launch: the library's fill kernel on 4 bytes, 200 launches per HIP graph
+    import paper_2512_17970_amd as cg
+    tiny = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    launch = lambda: cg.codegemm_workspace_init(tiny, 4, torch.cuda.current_stream().cuda_stream)
+    for _ in range(3):
+        launch()
+    g = graph_of(torch, launch, 200)
+    g.replay()
+    us0 = statistics.median(time_region(torch, g.replay, 1) for _ in range(5)) * 1e3 / 200
+    log(f"  a 4-byte fill kernel, back to back in a HIP graph: {us0:.2f} us per launch")
+    print(json.dumps({"memcpy": rows, "empty_launch_us": us0}))
 
 
 def phases_report(torch, cg, layers):
@@ -380,6 +390,7 @@ def main():
         psumbook_bench(torch, cg, synth)
         return
     if args.memcpy:
+        cg.load()
         memcpy_report(torch)
         return
     wl = synth.workloads()
