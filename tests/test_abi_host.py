@@ -41,6 +41,18 @@ def test_trace_library_exports_the_abi_and_the_trace_hook():
     assert not hasattr(cg.load(), "codegemm_set_trace")
 
 
+def test_ablation_libraries_export_the_abi():
+    """The ablation builds (parts of the batch-1 kernel compiled out, for ceiling studies) keep the whole ABI."""
+    from paper_2512_17970_amd import build as cg_build
+    for mask in cg_build.ABLATE_MASKS:
+        path = cg_build.ablate_lib(mask)
+        if not os.path.exists(path):
+            pytest.skip(f"{path} not built")
+        lib = ctypes.CDLL(path)
+        for s in header_symbols():
+            assert hasattr(lib, s), (mask, s)
+
+
 def test_phases_workgroup_count_matches_the_plan():
     from paper_2512_17970_amd import phases
     d = cg.Desc.make(1, 8192, 28672, 8, 2)
