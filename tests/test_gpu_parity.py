@@ -328,6 +328,50 @@ def test_batches_above_one_launch(B, K, N, v, m, g):
     run_case(synth.custom_case(K, N, v, m, B, seed=606 + B, g=g))
 
 
+@pytest.mark.parametrize("fill", [0, 255, 128])
+def test_constant_codes_extreme_indices(fill):
+    """Every code the same index (0, 255 and 128: the ends of the table and the sign bit of the code
+    byte): all lanes of a half-wavefront read one Psumbook row, and the byte-permute address assembly
+    sees its extreme values.  Batch 1, 2 (code words reused for a second Psumbook) and 5 (batched kernel)."""
+    for (v, m, B) in [(8, 2, 1), (4, 1, 1), (8, 3, 2), (16, 4, 1), (8, 2, 5)]:
+        case = synth.custom_case(v * 32 * 9 + v * 3, 777, v, m, B, seed=400 + fill)
+        inp = synth.generate(case)
+        inp.codes = np.full_like(inp.codes, fill)
+        say(f"[constant codes {fill}] {case.name}")
+        y_ref, T = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+        layer = DeviceLayer(inp)
+        y = layer.gemm()
+        torch.cuda.synchronize()
+        check_against_oracle(y.cpu().numpy(), y_ref, T, f"constant codes {fill} {case.name}")
+
+
+def test_wide_dynamic_range_inputs():
+    """Activations and centroids spread over many binades (lognormal magnitudes, up to the top of the
+    fp16 range for x): fp16 x fp16 products stay exact in fp32 and the fp32 sums must still meet the
+    per-element bound; fp32 output, so that nothing overflows fp16 on the way out."""
+    rng = np.random.default_rng(77)
+    for (v, m, B, g) in [(8, 2, 1, -1), (4, 1, 1, 32), (8, 2, 4, -1), (16, 3, 1, -1)]:
+        case = synth.custom_case(v * 32 * 12, 900, v, m, B, seed=78, g=g)
+        inp = synth.generate(case)
+        mag = np.exp(rng.normal(0.0, 3.0, inp.x.shape)).clip(2.0 ** -14, 60000.0)
+        inp.x = (np.sign(rng.standard_normal(inp.x.shape)) * mag).astype(np.float16)
+        cmag = np.exp(rng.normal(-4.0, 2.5, inp.codebooks.shape)).clip(2.0 ** -20, 8.0)
+        inp.codebooks = (np.sign(rng.standard_normal(inp.codebooks.shape)) * cmag).astype(np.float16)
+        say(f"[dynamic range] {case.name}")
+        y_ref, T = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+        layer = DeviceLayer(inp, y_fp32=True)
+        y = layer.gemm()
+        torch.cuda.synchronize()
+        got = y.cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(got))
+        assert np.all(np.abs(got - y_ref) <= 1e-5 * T + 1e-30)           # fp32 accumulation: ~K*2^-24 of sum|terms| at worst
+        for b in range(case.B):
+            assert np.linalg.norm(got[b] - y_ref[b]) <= 1e-3 * np.linalg.norm(y_ref[b])
+        yd = layer.dequant()
+        torch.cuda.synchronize()
+        assert np.all(np.abs(yd.cpu().numpy().astype(np.float64) - y_ref) <= 1e-5 * T + 1e-30)
+
+
 def test_random_formats_shapes_and_plans():
     """Seeded random draws over the whole supported space: format (v, m, g), shape (ragged N and K),
     batch, and launch plan (any plan the library accepts for the format)."""
