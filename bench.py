@@ -173,17 +173,35 @@ def per_shape_detail(torch, layers, launch):
     return rows
 
 
+def group_detail(torch, group, launch, n=100):
+    """Cold time of one grouped launch (every call streams other copies of its members' codes)."""
+    for _ in range(10):
+        group.gemm()
+    if launch == "graph":
+        group.i = 0
+        g = graph_of(torch, group.gemm, n)
+        ts = [time_region(torch, g.replay, 1) * 1e3 / n for _ in range(5)]
+    else:
+        ts = [time_region(torch, group.gemm, n) * 1e3 / n for _ in range(5)]
+    nbytes = sum(L.bytes for L, _ in group.members)
+    row = {"members": [L.case.name for L, _ in group.members], "plan": repr(group.plan), "compressed_bytes": nbytes,
+           "us_cold_min": min(ts), "GBps_cold": nbytes / min(ts) * 1e-3, "frac_of_peak_cold": nbytes / min(ts) * 1e-3 / HBM_PEAK_GBPS}
+    log(f"  grouped {'+'.join(str(n_) for n_ in group.Ns)} rows {row['plan']}: cold {row['us_cold_min']:.2f} us "
+        f"({row['GBps_cold']:.0f} GB/s, {100 * row['frac_of_peak_cold']:.1f}% of peak)")
+    return row
+
+
 def decoder_block_us(torch, layers, order, launch, blocks=30, runs=5):
     """All linear layers of one decoder block launched back to back on one stream, every launch
     on another copy of its weights: `blocks` blocks per timed run (one HIP graph), median of `runs`."""
     def block():
         for i in order:
-            layers[i].gemm()
+            (layers[i] if isinstance(i, int) else i).gemm()
 
     for _ in range(3):
         block()
     if launch == "graph":
-        for L in layers:
+        for L in list(layers) + [i for i in order if not isinstance(i, int)]:
             L.i = 0
         g = graph_of(torch, lambda: [block() for _ in range(blocks)], 1)
         g.replay()
@@ -191,6 +209,36 @@ def decoder_block_us(torch, layers, order, launch, blocks=30, runs=5):
     else:
         ts = [time_region(torch, block, blocks) for _ in range(runs)]
     return statistics.median(ts) * 1e3 / blocks
+
+
+class Group:
+    """Layers that read the same x (q/k/v, or gate/up) run as one grouped launch; members are
+    (layer, copy offset) pairs, so that two members of one shape stream different copies."""
+
+    def __init__(self, cg, torch, members):
+        self.cg, self.torch, self.members = cg, torch, members
+        first = members[0][0]
+        c = first.case
+        self.Ns = [L.case.N for L, _ in members]
+        self.desc = cg.Desc.make(c.B, c.K, sum(self.Ns), c.v, c.m, g=c.g)
+        self.plan = cg.codegemm_default_plan(self.desc)
+        self.x = first.x
+        self.ys = [torch.empty((c.B, n), dtype=torch.float16, device="cuda") for n in self.Ns]
+        self.ws_bytes = cg.codegemm_grouped_workspace_bytes(self.desc, self.plan, self.Ns)
+        if self.ws_bytes == 0:
+            raise SystemExit(f"no grouped launch for {c.name} under {self.plan}")
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device="cuda")
+        cg.codegemm_workspace_init(self.ws, self.ws_bytes, torch.cuda.current_stream().cuda_stream)
+        self.i = 0
+
+    def gemm(self):
+        mem = []
+        for (L, off), n, y in zip(self.members, self.Ns, self.ys):
+            r = (self.i * 2 + off) % L.R
+            mem.append((n, L.packed[r], L.codebooks, L.gemm_scales[r], y))
+        self.i += 1
+        self.cg.codegemm_gemm_grouped(self.desc, self.plan, self.x, mem, self.ws, self.ws_bytes,
+                                      self.torch.cuda.current_stream().cuda_stream)
 
 
 def cpu_baseline(cases, synth, budget_s=12.0):
@@ -471,6 +519,14 @@ def main():
             out["config"]["decoder_block_us"] = round(decoder_block_us(torch, layers, order, args.launch), 3)
             log(f"decoder block, {len(order)} linears launched back to back (timed): {out['config']['decoder_block_us']:.2f} us; "
                 f"sum of the per-shape times: {out['config']['decoder_block_sum_us']:.2f} us")
+            if key in ("c2", "c3", "c7", "c8") and all(L.plan.batch_group != 4 for L in layers):
+                # the same seven layers as four launches: q, k and v grouped, o, gate and up grouped, down
+                gorder = [Group(cg, torch, [(layers[0], 0), (layers[1], 0), (layers[1], 1)]), 0,
+                          Group(cg, torch, [(layers[2], 0), (layers[2], 1)]), 3]
+                out["config"]["grouped_launches"] = [group_detail(torch, gr, args.launch) for gr in gorder if not isinstance(gr, int)]
+                out["config"]["decoder_block_grouped_us"] = round(decoder_block_us(torch, layers, gorder, args.launch), 3)
+                log(f"decoder block with grouped launches (q,k,v | o | gate,up | down): "
+                    f"{out['config']['decoder_block_grouped_us']:.2f} us")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cases, synth)
         log(f"cpu oracle: {out['cpu_baseline']['ms_per_step']:.1f} ms per step on {out['cpu_baseline']['cores']} threads")

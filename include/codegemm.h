@@ -211,6 +211,44 @@ int codegemm_gemm(const codegemm_desc *desc, const codegemm_plan *plan,
                   void *stream);
 
 /*
+ * The hot path for up to 4 layers that read the same x in ONE kernel launch:
+ * the q, k and v projections of a decoder block, or its gate and up projections
+ * (the paper times a whole decoder block, Section 4.1 and its latency table; at
+ * batch 1 a launch costs about as much as a small layer's data movement).  The
+ * layers share in_features, the format (v, m, group_size), the batch and the
+ * flags; each has its own out_features, packed codes, codebooks, scales and y.
+ * Member i's result is bit-identical to codegemm_gemm on that layer alone with
+ * the same plan.
+ *   desc->out_features   the SUM of the members' out_features (checked);
+ *   plan                 required (not NULL): codegemm_default_plan(desc) suits,
+ *                        since the launch fills the chip like one layer of the
+ *                        summed height; batch_group must be 1 or 2 (so batch <= 2
+ *                        under default plans), batch <= 32;
+ *   group[i]             device pointers as for codegemm_gemm, y [batch][out_features_i];
+ *   workspace            codegemm_grouped_workspace_bytes() bytes, initialised once
+ *                        with codegemm_workspace_init; any workspace may be shared
+ *                        between grouped and plain calls on one stream.
+ * Errors: CODEGEMM_INVALID_ARG (count outside 1..4, null or misaligned pointer,
+ * out_features not summing to desc->out_features), CODEGEMM_UNSUPPORTED (batched
+ * kernel plan, batch > 32, more than 65535 row blocks), CODEGEMM_WORKSPACE_TOO_SMALL.
+ * codegemm_grouped_workspace_bytes returns 0 on any of the former two.
+ */
+typedef struct codegemm_group_member {
+    int32_t out_features;
+    int32_t reserved;             /* 0 */
+    const uint8_t *packed_codes;  /* device, output of codegemm_pack_codes for this layer */
+    const void *codebooks;        /* device, [m][256][v] fp16 */
+    const void *scales;           /* device, [N] fp16 or the output of codegemm_pack_scales */
+    void *y;                      /* device, [batch][out_features] */
+} codegemm_group_member;
+
+size_t codegemm_grouped_workspace_bytes(const codegemm_desc *desc, const codegemm_plan *plan,
+                                        const int32_t *out_features, int32_t count);
+int codegemm_gemm_grouped(const codegemm_desc *desc, const codegemm_plan *plan, const void *x,
+                          const codegemm_group_member *group, int32_t count,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * codegemm_gemm for callers that cannot allocate device memory or carry a
  * workspace around: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same computation, same kernels and the same

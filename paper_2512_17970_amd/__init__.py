@@ -13,4 +13,5 @@ from .binding import (  # noqa: F401
     codegemm_pack_scales,
     codegemm_pack_codes_host, codegemm_unpack_codes_host,
     codegemm_gemm_static, codegemm_static_workspace_limit,
+    GroupMember, codegemm_gemm_grouped, codegemm_grouped_workspace_bytes,
 )

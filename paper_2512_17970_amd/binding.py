@@ -26,6 +26,7 @@ EXPORTS = [
     "codegemm_packed_scales_bytes", "codegemm_pack_scales",
     "codegemm_psumbook_build", "codegemm_gemm", "codegemm_dequant_gemm", "codegemm_status_string",
     "codegemm_gemm_static", "codegemm_static_workspace_limit",
+    "codegemm_gemm_grouped", "codegemm_grouped_workspace_bytes",
 ]
 
 
@@ -59,6 +60,13 @@ class Plan(ctypes.Structure):
         tail = ", psum_dtype=fp16" if self.psum_dtype == PSUM_FP16 else ""
         return (f"Plan(waves={self.waves}, row_words={self.row_words}, k_splits={self.k_splits}, "
                 f"batch_group={self.batch_group}{tail})")
+
+
+class GroupMember(ctypes.Structure):
+    """codegemm_group_member of include/codegemm.h: one layer of a grouped launch."""
+    _fields_ = [("out_features", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("packed_codes", ctypes.c_void_p), ("codebooks", ctypes.c_void_p),
+                ("scales", ctypes.c_void_p), ("y", ctypes.c_void_p)]
 
 
 def lib_path() -> str:
@@ -111,6 +119,10 @@ def load() -> ctypes.CDLL:
     lib.codegemm_gemm.restype = i
     lib.codegemm_gemm_static.argtypes = [dp, pp, vp, vp, vp, vp, vp, vp]
     lib.codegemm_gemm_static.restype = i
+    lib.codegemm_gemm_grouped.argtypes = [dp, pp, vp, ctypes.POINTER(GroupMember), ctypes.c_int32, vp, sz, vp]
+    lib.codegemm_gemm_grouped.restype = i
+    lib.codegemm_grouped_workspace_bytes.argtypes = [dp, pp, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32]
+    lib.codegemm_grouped_workspace_bytes.restype = sz
     lib.codegemm_static_workspace_limit.argtypes = []
     lib.codegemm_static_workspace_limit.restype = sz
     lib.codegemm_dequant_gemm.argtypes = [dp, vp, vp, vp, vp, vp, vp]
@@ -217,6 +229,25 @@ def codegemm_static_workspace_limit() -> int:
 def codegemm_gemm_static(desc: Desc, plan: Optional[Plan], x, packed_codes, codebooks, scales, y, stream: int = 0) -> None:
     _check(load().codegemm_gemm_static(ctypes.byref(desc), _plan(plan), _ptr(x), _ptr(packed_codes), _ptr(codebooks),
                                        _ptr(scales), _ptr(y), ctypes.c_void_p(stream)), "codegemm_gemm_static")
+
+
+def codegemm_grouped_workspace_bytes(desc: Desc, plan: Plan, out_features) -> int:
+    arr = (ctypes.c_int32 * len(out_features))(*out_features)
+    return int(load().codegemm_grouped_workspace_bytes(ctypes.byref(desc), _plan(plan), arr, len(out_features)))
+
+
+def codegemm_gemm_grouped(desc: Desc, plan: Plan, x, members, workspace, workspace_bytes: int, stream: int = 0) -> None:
+    """members: sequence of (out_features, packed_codes, codebooks, scales, y), tensors or raw device addresses."""
+    arr = (GroupMember * len(members))()
+    for k, (n, packed, codebooks, scales, y) in enumerate(members):
+        arr[k].out_features = n
+        arr[k].reserved = 0
+        arr[k].packed_codes = _ptr(packed).value
+        arr[k].codebooks = _ptr(codebooks).value
+        arr[k].scales = _ptr(scales).value
+        arr[k].y = _ptr(y).value
+    _check(load().codegemm_gemm_grouped(ctypes.byref(desc), _plan(plan), _ptr(x), arr, len(members),
+                                        _ptr(workspace), workspace_bytes, ctypes.c_void_p(stream)), "codegemm_gemm_grouped")
 
 
 def codegemm_dequant_gemm(desc: Desc, x, codes, codebooks, scales, y, stream: int = 0) -> None:

@@ -70,42 +70,9 @@ static uint64_t* g_trace = nullptr;
 extern "C" void codegemm_set_trace(uint64_t* stamps) { g_trace = stamps; }
 #endif
 
-// One launch: at most kBatchPerLaunch batch rows.
-static int gemm_launch(const codegemm_desc* desc, const codegemm_plan* plan, const void* x,
-                       const uint8_t* packed_codes, const void* codebooks, const void* scales,
-                       void* y, void* workspace, size_t workspace_bytes, void* stream)
+// Kernel instance for a geometry -> launch.  g.NBLK is the number of row blocks of all members of p.
+static int dispatch(const Geometry& g, const GemmParams& p, hipStream_t s)
 {
-    Geometry g;
-    int st = make_geometry(desc, plan, &g);
-    if (st) return st;
-    if (!x || !packed_codes || !codebooks || !scales || !y || !workspace) return CODEGEMM_INVALID_ARG;
-    if (misaligned(x) || misaligned(packed_codes) || misaligned(codebooks) || misaligned(scales) ||
-        misaligned(y) || misaligned(workspace))
-        return CODEGEMM_INVALID_ARG;
-    const size_t cbytes = workspace_counter_bytes(g);
-    const size_t need = cbytes + (size_t)g.B * g.NKS * g.Npad * sizeof(float);
-    if (workspace_bytes < need) return CODEGEMM_WORKSPACE_TOO_SMALL;
-
-    GemmParams p;
-    p.x = static_cast<const _Float16*>(x);
-    p.packed = packed_codes;
-    p.codebooks = static_cast<const _Float16*>(codebooks);
-    p.scales = g.g > 0 ? nullptr : static_cast<const _Float16*>(scales);
-    p.gscales = g.g > 0 ? static_cast<const uint8_t*>(scales) : nullptr;
-    p.GPU = g.GPU;
-    p.gshift = g.gshift;
-    p.y = y;
-    p.counters = static_cast<uint32_t*>(workspace);
-    p.cstride = counter_stride(g);
-    p.partials = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + cbytes);
-    p.B = g.B; p.K = g.K; p.N = g.N;
-    p.NGR = g.NGR; p.NKT = g.NKT; p.NKS = g.NKS; p.KPW = g.KPW; p.Npad = g.Npad;
-    p.y_fp32 = g.y_fp32 ? 1 : 0;
-    p.trace = nullptr;
-#ifdef CODEGEMM_TRACE
-    p.trace = reinterpret_cast<unsigned long long*>(g_trace);
-#endif
-    hipStream_t s = static_cast<hipStream_t>(stream);
     if (g.BG == 4) {
         switch (g.m) {
             case 1: return g.g > 0 ? launch_gemm_batch_gs_m1(g, p, s) : launch_gemm_batch_m1(g, p, s);
@@ -140,6 +107,61 @@ static int gemm_launch(const codegemm_desc* desc, const codegemm_plan* plan, con
         case 4: return launch_gemm_m4(g, p, s);
     }
     return CODEGEMM_UNSUPPORTED;
+}
+
+// The fields of the kernel arguments that all members of a launch share.
+static void fill_common(GemmParams* p, const Geometry& g, const void* x, void* workspace)
+{
+    p->x = static_cast<const _Float16*>(x);
+    p->GPU = g.GPU;
+    p->gshift = g.gshift;
+    p->counters = static_cast<uint32_t*>(workspace);
+    p->cstride = counter_stride(g);
+    p->B = g.B; p->K = g.K;
+    p->NKT = g.NKT; p->NKS = g.NKS; p->KPW = g.KPW;
+    p->y_fp32 = g.y_fp32 ? 1 : 0;
+    p->trace = nullptr;
+#ifdef CODEGEMM_TRACE
+    p->trace = reinterpret_cast<unsigned long long*>(g_trace);
+#endif
+    p->ngrp = 1;
+    for (int i = 0; i < kMaxGroup; ++i) p->mem[i] = Member{};
+}
+
+static void fill_member(Member* mm, const Geometry& g, const uint8_t* packed_codes, const void* codebooks,
+                        const void* scales, void* y, float* partials, int blk0)
+{
+    mm->packed = packed_codes;
+    mm->codebooks = static_cast<const _Float16*>(codebooks);
+    mm->scales = g.g > 0 ? nullptr : static_cast<const _Float16*>(scales);
+    mm->gscales = g.g > 0 ? static_cast<const uint8_t*>(scales) : nullptr;
+    mm->y = y;
+    mm->partials = partials;
+    mm->N = g.N; mm->NGR = g.NGR; mm->Npad = g.Npad;
+    mm->blk0 = blk0;
+}
+
+// One launch: at most kBatchPerLaunch batch rows.
+static int gemm_launch(const codegemm_desc* desc, const codegemm_plan* plan, const void* x,
+                       const uint8_t* packed_codes, const void* codebooks, const void* scales,
+                       void* y, void* workspace, size_t workspace_bytes, void* stream)
+{
+    Geometry g;
+    int st = make_geometry(desc, plan, &g);
+    if (st) return st;
+    if (!x || !packed_codes || !codebooks || !scales || !y || !workspace) return CODEGEMM_INVALID_ARG;
+    if (misaligned(x) || misaligned(packed_codes) || misaligned(codebooks) || misaligned(scales) ||
+        misaligned(y) || misaligned(workspace))
+        return CODEGEMM_INVALID_ARG;
+    const size_t cbytes = workspace_counter_bytes(g);
+    const size_t need = cbytes + (size_t)g.B * g.NKS * g.Npad * sizeof(float);
+    if (workspace_bytes < need) return CODEGEMM_WORKSPACE_TOO_SMALL;
+
+    GemmParams p;
+    fill_common(&p, g, x, workspace);
+    fill_member(&p.mem[0], g, packed_codes, codebooks, scales, y,
+                reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + cbytes), 0);
+    return dispatch(g, p, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int codegemm_gemm(const codegemm_desc* desc, const codegemm_plan* plan, const void* x,
@@ -184,4 +206,80 @@ extern "C" int codegemm_gemm_static(const codegemm_desc* desc, const codegemm_pl
     const int st = static_workspace(&ws, static_cast<hipStream_t>(stream));
     if (st) return st;
     return codegemm_gemm(desc, plan, x, packed_codes, codebooks, scales, y, ws, kStaticWorkspaceBytes, stream);
+}
+
+// ---- several layers that share x in one launch ----------------------------------------------
+
+// Geometry of the members of a group under one plan, and the geometry of the whole launch (row
+// blocks summed).  The plan has to suit every member, batch rows go through the gather kernel
+// that handles one or two of them per pass, and a launch takes at most kBatchPerLaunch rows.
+static int group_geometry(const codegemm_desc* desc, const codegemm_plan* plan, const int32_t* out_features,
+                          int count, Geometry* members, Geometry* whole)
+{
+    if (!desc || !plan || !out_features) return CODEGEMM_INVALID_ARG;
+    if (count < 1 || count > kMaxGroup) return CODEGEMM_INVALID_ARG;
+    if (desc->batch > kBatchPerLaunch) return CODEGEMM_UNSUPPORTED;
+    long long total = 0;
+    for (int i = 0; i < count; ++i) {
+        codegemm_desc d = *desc;
+        d.out_features = out_features[i];
+        const int st = make_geometry(&d, plan, &members[i]);
+        if (st) return st;
+        total += out_features[i];
+    }
+    if (total != desc->out_features) return CODEGEMM_INVALID_ARG;
+    if (members[0].BG == 4) return CODEGEMM_UNSUPPORTED;
+    *whole = members[0];
+    whole->N = (int)total;
+    whole->NBLK = 0; whole->NGR = 0; whole->Npad = 0;
+    for (int i = 0; i < count; ++i) {
+        whole->NBLK += members[i].NBLK;
+        whole->NGR += members[i].NGR;
+        whole->Npad += members[i].Npad;
+    }
+    if (whole->NBLK > 65535 || counter_stride(*whole) == 0) return CODEGEMM_UNSUPPORTED;
+    return CODEGEMM_OK;
+}
+
+extern "C" size_t codegemm_grouped_workspace_bytes(const codegemm_desc* desc, const codegemm_plan* plan,
+                                                   const int32_t* out_features, int32_t count)
+{
+    Geometry members[kMaxGroup], whole;
+    if (group_geometry(desc, plan, out_features, count, members, &whole)) return 0;
+    return workspace_counter_bytes(whole) + (size_t)whole.B * whole.NKS * whole.Npad * sizeof(float);
+}
+
+extern "C" int codegemm_gemm_grouped(const codegemm_desc* desc, const codegemm_plan* plan, const void* x,
+                                     const codegemm_group_member* group, int32_t count,
+                                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!group || count < 1 || count > kMaxGroup) return CODEGEMM_INVALID_ARG;
+    int32_t out_features[kMaxGroup];
+    for (int i = 0; i < count; ++i) out_features[i] = group[i].out_features;
+    Geometry members[kMaxGroup], whole;
+    int st = group_geometry(desc, plan, out_features, count, members, &whole);
+    if (st) return st;
+    if (!x || !workspace || misaligned(x) || misaligned(workspace)) return CODEGEMM_INVALID_ARG;
+    for (int i = 0; i < count; ++i) {
+        const codegemm_group_member& gm = group[i];
+        if (!gm.packed_codes || !gm.codebooks || !gm.scales || !gm.y) return CODEGEMM_INVALID_ARG;
+        if (misaligned(gm.packed_codes) || misaligned(gm.codebooks) || misaligned(gm.scales) || misaligned(gm.y))
+            return CODEGEMM_INVALID_ARG;
+    }
+    const size_t cbytes = workspace_counter_bytes(whole);
+    const size_t need = cbytes + (size_t)whole.B * whole.NKS * whole.Npad * sizeof(float);
+    if (workspace_bytes < need) return CODEGEMM_WORKSPACE_TOO_SMALL;
+
+    GemmParams p;
+    fill_common(&p, whole, x, workspace);
+    p.ngrp = count;
+    float* partials = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + cbytes);
+    int blk0 = 0;
+    for (int i = 0; i < count; ++i) {
+        fill_member(&p.mem[i], members[i], group[i].packed_codes, group[i].codebooks, group[i].scales,
+                    group[i].y, partials, blk0);
+        partials += (size_t)whole.B * whole.NKS * members[i].Npad;
+        blk0 += members[i].NBLK;
+    }
+    return dispatch(whole, p, static_cast<hipStream_t>(stream));
 }

@@ -75,6 +75,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be: keeps buffer descriptors in scalar registers
     const int ks = blockIdx.x;
+    const Member mm = p.mem[0];                        // batched launches hold one layer
     const int blk = blockIdx.y;                        // row block of GPW granules
     const int b0 = blockIdx.z * BG;
     const int kt0 = ks * p.KPW;
@@ -113,7 +114,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
         int t = wave + i * NW;
         if (t >= NBLOCKS) t = NBLOCKS - 1;
         const int cb = (M == 1) ? 0 : t / 8;
-        cfrag[i] = *reinterpret_cast<const frag_t*>(p.codebooks + (size_t)((cb * 8 + t % 8) * 32 + (lane & 31)) * V + (kvalid ? FE * khalf : 0));
+        cfrag[i] = *reinterpret_cast<const frag_t*>(mm.codebooks + (size_t)((cb * 8 + t % 8) * 32 + (lane & 31)) * V + (kvalid ? FE * khalf : 0));
     }
     // Activation operand (Step 1): column n = lane % 32 of a block is (slot n / 4, batch row
     // n % 4); the lane supplies elements 4 * (lane / 32)..+3 of that sub-vector.  One
@@ -148,8 +149,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
 #pragma unroll
     for (int q = 0; q < RPL; ++q) {
         const int gr = blk * GPW + q * (NW / 4) + wave / 4;
-        const uint8_t* base = p.packed + ((size_t)min(gr, p.NGR - 1) * p.NKT + kt0) * kUnitBytes;
-        c_rsrc[q] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, gr < p.NGR ? nq * kUnitBytes : 0, kRsrcFlags);
+        const uint8_t* base = mm.packed + ((size_t)min(gr, mm.NGR - 1) * p.NKT + kt0) * kUnitBytes;
+        c_rsrc[q] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, gr < mm.NGR ? nq * kUnitBytes : 0, kRsrcFlags);
     }
     int c_off[SP];
 #pragma unroll
@@ -181,8 +182,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
 #pragma unroll
         for (int q = 0; q < RPL; ++q) {
             const int gr = blk * GPW + q * (NW / 4) + wave / 4;
-            const uint8_t* base = p.gscales + ((size_t)min(gr, p.NGR - 1) * p.NKT + kt0) * p.GPU * 256;
-            s_rsrc[q] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, gr < p.NGR ? nq * p.GPU * 256 : 0, kRsrcFlags);
+            const uint8_t* base = mm.gscales + ((size_t)min(gr, mm.NGR - 1) * p.NKT + kt0) * p.GPU * 256;
+            s_rsrc[q] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, gr < mm.NGR ? nq * p.GPU * 256 : 0, kRsrcFlags);
         }
     }
     auto load_scales = [&](half8_t (&dst)[RPL], int t) {
@@ -310,7 +311,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
             stage[(bb + 1) * ROWS + local] = v[1];
         }
     }
-    finish_block<NW * kWave, BG, ROWS>(p, stage, flag, tid, blk, ks, b0);
+    finish_block<NW * kWave, BG, ROWS>(p, mm, stage, flag, tid, blk, ks, b0);
 }
 
 template <int M, int V, int NW, int RPL, int D, bool GS>

@@ -47,22 +47,47 @@
 
 namespace cg {
 
-struct GemmParams {
-    const _Float16* x;
+constexpr int kMaxGroup = 4;     // layers one grouped launch can hold
+
+// What differs between the layers of one launch: a plain call has one member, a grouped call
+// (layers that share x and the format, e.g. the q, k and v projections) up to kMaxGroup, whose
+// row blocks follow each other along grid.y.
+struct Member {
     const uint8_t* packed;
     const _Float16* codebooks;
     const _Float16* scales;      // [N], one per output row; nullptr when group scales are used
     const uint8_t* gscales;      // packed group scales (see codegemm_pack_scales), or nullptr
     void* y;
     float* partials;             // [B][NKS][Npad]
-    uint32_t* counters;          // [groups][row blocks][cstride], word 0 of each is the ticket counter
+    int N, NGR, Npad;
+    int blk0;                    // first row block of this member in grid.y
+};
+
+struct GemmParams {
+    const _Float16* x;
+    uint32_t* counters;          // [groups][row blocks of all members][cstride], word 0 of each is the ticket counter
     int cstride;
-    int B, K, N;
-    int NGR, NKT, NKS, KPW, Npad;
+    int B, K;
+    int NKT, NKS, KPW;
     int y_fp32;
     int GPU, gshift;             // scale groups per unit; a lane's group in its unit = slot >> gshift
     unsigned long long* trace;   // [grid][24] timestamps (100 MHz) when built with CODEGEMM_TRACE, else unused
+    int ngrp;                    // members in use (1 for a plain call)
+    Member mem[kMaxGroup];
 };
+
+// The member a row block of the grid belongs to (uniform; constant indices only, so the table
+// stays in the kernel-argument segment).
+__device__ __forceinline__ Member member_of(const GemmParams& p, int grid_blk)
+{
+    Member m = p.mem[0];
+    if (p.ngrp > 1) {
+        if (grid_blk >= p.mem[1].blk0) m = p.mem[1];
+        if (p.ngrp > 2 && grid_blk >= p.mem[2].blk0) m = p.mem[2];
+        if (p.ngrp > 3 && grid_blk >= p.mem[3].blk0) m = p.mem[3];
+    }
+    return m;
+}
 
 #ifdef CODEGEMM_TRACE
 #define CG_STAMP(k) do { if (p.trace && threadIdx.x == 0 && blockIdx.z == 0) p.trace[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 24 + (k)] = wall_clock64(); } while (0)
@@ -338,7 +363,7 @@ __device__ __forceinline__ float halfwave_transpose_sum(float (&v)[NV], int lane
 // the row block's counter, and the last one to arrive adds the partials of all K ranges in
 // range order, scales and stores y.  Ends with the kernel: every path returns.
 template <int NT, int BG, int ROWS>
-__device__ __forceinline__ void finish_block(const GemmParams& p, const float* stage, uint32_t* flag,
+__device__ __forceinline__ void finish_block(const GemmParams& p, const Member& mm, const float* stage, uint32_t* flag,
                                              int tid, int blk, int ks, int b0)
 {
     CG_STAMP(16);
@@ -355,7 +380,7 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
         const int nn = n_base + o % ROWS;
         mine[i] = (o < BG * ROWS) ? stage[o] : 0.0f;
         // requested before any ticket round trip; with group scales the totals are already scaled
-        scale_bits[i] = p.scales ? reinterpret_cast<const uint16_t*>(p.scales)[nn < p.N ? nn : 0] : 0x3c00u;
+        scale_bits[i] = mm.scales ? reinterpret_cast<const uint16_t*>(mm.scales)[nn < mm.N ? nn : 0] : 0x3c00u;
     }
     // The scale is first touched where it is used (the pin keeps its conversion, and with it
     // the wait for the load, from being hoisted in front of the partial-sum stores).
@@ -365,8 +390,8 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
         return (float)__builtin_bit_cast(_Float16, (uint16_t)b);
     };
     auto store_y = [&](int row, int nn, float val) {
-        if (p.y_fp32) static_cast<float*>(p.y)[(size_t)row * p.N + nn] = val;
-        else static_cast<_Float16*>(p.y)[(size_t)row * p.N + nn] = (_Float16)val;
+        if (p.y_fp32) static_cast<float*>(mm.y)[(size_t)row * mm.N + nn] = val;
+        else static_cast<_Float16*>(mm.y)[(size_t)row * mm.N + nn] = (_Float16)val;
     };
 
 #if CODEGEMM_ABLATE & 8
@@ -379,7 +404,7 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
         for (int i = 0; i < PER_THREAD; ++i) {
             const int o = tid + i * NT;
             const int row = b0 + o / ROWS, nn = n_base + o % ROWS;
-            if (o < BG * ROWS && row < p.B && nn < p.N) store_y(row, nn, mine[i] * scale_of(i));
+            if (o < BG * ROWS && row < p.B && nn < mm.N) store_y(row, nn, mine[i] * scale_of(i));
         }
         CG_STAMP(3);
         return;
@@ -394,8 +419,8 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
     for (int i = 0; i < PER_THREAD; ++i) {
         const int o = tid + i * NT;
         const int row = b0 + o / ROWS, nn = n_base + o % ROWS;
-        if (o < BG * ROWS && row < p.B && nn < p.Npad)
-            __hip_atomic_store(p.partials + ((size_t)row * p.NKS + ks) * p.Npad + nn, mine[i],
+        if (o < BG * ROWS && row < p.B && nn < mm.Npad)
+            __hip_atomic_store(mm.partials + ((size_t)row * p.NKS + ks) * mm.Npad + nn, mine[i],
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     CG_STAMP(5);
@@ -403,7 +428,7 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
     __syncthreads();
     CG_STAMP(6);
     if (tid == 0) {
-        uint32_t* ctr = p.counters + ((size_t)blockIdx.z * gridDim.y + blk) * p.cstride;
+        uint32_t* ctr = p.counters + ((size_t)blockIdx.z * gridDim.y + mm.blk0 + blk) * p.cstride;
         const uint32_t old = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const bool last = old == (uint32_t)(p.NKS - 1);
         if (last) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
@@ -417,15 +442,15 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
     for (int i = 0; i < PER_THREAD; ++i) {
         const int o = tid + i * NT;
         const int row = b0 + o / ROWS, nn = n_base + o % ROWS;
-        if (o >= BG * ROWS || row >= p.B || nn >= p.N) continue;
-        const float* src = p.partials + (size_t)row * p.NKS * p.Npad + nn;
+        if (o >= BG * ROWS || row >= p.B || nn >= mm.N) continue;
+        const float* src = mm.partials + (size_t)row * p.NKS * mm.Npad + nn;
         float sum = 0.0f;
         int k2 = 0;
         for (; k2 + 32 <= p.NKS; k2 += 32) {            // 32 loads in flight, added in range order
             float v[32];
 #pragma unroll
             for (int j = 0; j < 32; ++j)
-                v[j] = __hip_atomic_load(src + (size_t)(k2 + j) * p.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                v[j] = __hip_atomic_load(src + (size_t)(k2 + j) * mm.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
             for (int j = 0; j < 32; ++j) sum += v[j];
         }
@@ -433,7 +458,7 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
             float v[16];
 #pragma unroll
             for (int j = 0; j < 16; ++j)
-                v[j] = __hip_atomic_load(src + (size_t)(k2 + j) * p.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                v[j] = __hip_atomic_load(src + (size_t)(k2 + j) * mm.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
             for (int j = 0; j < 16; ++j) sum += v[j];
         }
@@ -441,7 +466,7 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
             float v[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j)
-                v[j] = __hip_atomic_load(src + (size_t)(k2 + j) * p.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                v[j] = __hip_atomic_load(src + (size_t)(k2 + j) * mm.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
             for (int j = 0; j < 8; ++j) sum += v[j];
         }
@@ -449,12 +474,12 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const float* s
             float v[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                v[j] = __hip_atomic_load(src + (size_t)(k2 + j) * p.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                v[j] = __hip_atomic_load(src + (size_t)(k2 + j) * mm.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
             for (int j = 0; j < 4; ++j) sum += v[j];
         }
         for (; k2 < p.NKS; ++k2)
-            sum += __hip_atomic_load(src + (size_t)k2 * p.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sum += __hip_atomic_load(src + (size_t)k2 * mm.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         store_y(row, nn, sum * scale_of(i));
     }
     CG_STAMP(3);
@@ -495,7 +520,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be: keeps buffer descriptors in scalar registers
     const int ks = blockIdx.x;
-    const int blk = blockIdx.y;                        // row block of GPW granules
+    const Member mm = member_of(p, blockIdx.y);        // the layer this workgroup works for
+    const int blk = blockIdx.y - mm.blk0;              // its row block of GPW granules
     const int b0 = blockIdx.z * BG;
     const int kt0 = ks * p.KPW;
     const int nq = min(p.KPW, p.NKT - kt0);            // units of this workgroup (>= 1 by construction)
@@ -522,7 +548,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
         for (int i = 0; i < TPW; ++i) {
             int tile = wave + i * NW;                      // c*8 + iblk
             if (tile >= NTILES) tile = NTILES - 1;
-            cfrag[i] = *reinterpret_cast<const frag_t*>(p.codebooks + (size_t)(tile * 32 + (lane & 31)) * V + (kvalid ? FE * khalf : 0));
+            cfrag[i] = *reinterpret_cast<const frag_t*>(mm.codebooks + (size_t)(tile * 32 + (lane & 31)) * V + (kvalid ? FE * khalf : 0));
         }
     } else {
 #pragma unroll
@@ -532,7 +558,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const int c = min(2 * sp + h, M - 1);
-                cpair[i][h] = *reinterpret_cast<const frag_t*>(p.codebooks + (size_t)((c * 8 + iblk) * 32 + (lane & 31)) * V + (kvalid ? FE * khalf : 0));
+                cpair[i][h] = *reinterpret_cast<const frag_t*>(mm.codebooks + (size_t)((c * 8 + iblk) * 32 + (lane & 31)) * V + (kvalid ? FE * khalf : 0));
                 if (!kvalid || 2 * sp + h >= M) cpair[i][h] = zero4;           // an odd m leaves the last high half zero
             }
         }
@@ -567,8 +593,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
     for (int q = 0; q < RPL; ++q) {
         const int gr = granule_of(q);
         // a granule past the end of the matrix (ragged last block) gets an empty range: all codes read as 0
-        const uint8_t* base = p.packed + ((size_t)min(gr, p.NGR - 1) * p.NKT + kt0) * kUnitBytes;
-        c_rsrc[q] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, gr < p.NGR ? nq * kUnitBytes : 0, kRsrcFlags);
+        const uint8_t* base = mm.packed + ((size_t)min(gr, mm.NGR - 1) * p.NKT + kt0) * kUnitBytes;
+        c_rsrc[q] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, gr < mm.NGR ? nq * kUnitBytes : 0, kRsrcFlags);
     }
     auto load_codes = [&](uint32_t (&dst)[RPL][2 * M], int u) {
 #pragma unroll
@@ -599,8 +625,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
 #pragma unroll
         for (int q = 0; q < RPL; ++q) {
             const int gr = granule_of(q);
-            const uint8_t* base = p.gscales + ((size_t)min(gr, p.NGR - 1) * p.NKT + kt0) * p.GPU * 256;
-            s_rsrc[q] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, gr < p.NGR ? nq * p.GPU * 256 : 0, kRsrcFlags);
+            const uint8_t* base = mm.gscales + ((size_t)min(gr, mm.NGR - 1) * p.NKT + kt0) * p.GPU * 256;
+            s_rsrc[q] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, gr < mm.NGR ? nq * p.GPU * 256 : 0, kRsrcFlags);
         }
         s_off = ((lane & 31) >> p.gshift) * 256 + ((wave % 8) * 2 + khalf) * 16;
     }
@@ -808,7 +834,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
             }
         }
     }
-    finish_block<NW * kWave, BG, ROWS>(p, stage, flag, tid, blk, ks, b0);
+    finish_block<NW * kWave, BG, ROWS>(p, mm, stage, flag, tid, blk, ks, b0);
 }
 
 int set_max_lds(const void* fn, size_t bytes);

@@ -198,3 +198,24 @@ def test_fp16_psumbook_plans():
 def test_compressed_bytes_closed_form():
     # 8192 -> 28672, v8 m2, batch 1: codes 58,720,256 + codebooks 8192 + scales 57344 + x 16384 + y 57344
     assert cg.compressed_bytes(1, 8192, 28672, 8, 2) == 58720256 + 8192 + 57344 + 16384 + 57344
+
+
+def test_grouped_launch_host_validation():
+    """Sizes and refusals of the grouped launch that need no GPU."""
+    d = cg.Desc.make(1, 8192, 10240, 8, 2)
+    plan = cg.codegemm_default_plan(d)
+    Ns = [8192, 1024, 1024]
+    ws = cg.codegemm_grouped_workspace_bytes(d, plan, Ns)
+    # counter area + one fp32 partial per K range and padded row, member by member
+    pad = sum(-(-n // 128) * 128 for n in Ns)
+    assert ws == 65536 + plan.k_splits * pad * 4
+    assert cg.codegemm_grouped_workspace_bytes(d, plan, [8192, 1024]) == 0              # heights do not add up
+    assert cg.codegemm_grouped_workspace_bytes(d, plan, [8192, 1024, 512, 256, 256]) == 0   # more than four layers
+    assert cg.codegemm_grouped_workspace_bytes(d, plan, [10240, 0]) == 0                # an empty layer
+    assert cg.codegemm_grouped_workspace_bytes(d, cg.Plan.make(8, 1, 1, 4), Ns) == 0    # batched-kernel plan
+    d64 = cg.Desc.make(64, 8192, 10240, 8, 2)
+    assert cg.codegemm_grouped_workspace_bytes(d64, cg.Plan.make(8, 1, 1, 1), Ns) == 0  # more rows than one launch takes
+    # ragged members are padded one by one
+    d2 = cg.Desc.make(2, 1024, 130 + 129, 8, 2)
+    p2 = cg.Plan.make(8, 1, 2, 2)
+    assert cg.codegemm_grouped_workspace_bytes(d2, p2, [130, 129]) == 65536 + 2 * 2 * 512 * 4

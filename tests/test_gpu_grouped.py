@@ -1,0 +1,95 @@
+"""GPU parity of codegemm_gemm_grouped: several layers that share x in one launch.
+Every member's y is compared with the CPU oracle (the acceptance bar) and, bit for bit,
+with codegemm_gemm on that layer alone under the same plan."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+cg = pytest.importorskip("paper_2512_17970_amd")
+from gpu_util import DeviceLayer, Guarded, check_against_oracle, dev, stream  # noqa: E402
+
+
+def run_group(K, Ns, v, m, B, g, plan=None, seed=7000, y_fp32=False):
+    total = sum(Ns)
+    desc = cg.Desc.make(B, K, total, v, m, y_fp32=y_fp32, g=g)
+    if plan is None:
+        plan = cg.codegemm_default_plan(desc)
+    print(f"[grouped] K={K} Ns={Ns} v={v} m={m} B={B} g={g} {plan}", flush=True)
+    inps = [synth.generate(synth.custom_case(K, n, v, m, B, seed=seed + i, g=g)) for i, n in enumerate(Ns)]
+    x = inps[0].x
+    layers = []
+    for inp in inps:
+        inp.x = x                                            # the layers of a group read the same activations
+        layers.append(DeviceLayer(inp, plan=plan, y_fp32=y_fp32))
+    ws_bytes = cg.codegemm_grouped_workspace_bytes(desc, plan, Ns)
+    assert ws_bytes > 0
+    ws = Guarded(ws_bytes)
+    cg.codegemm_workspace_init(ws.t, ws_bytes, stream())
+    ys = [l.new_y() for l in layers]
+    members = [(n, l.packed, l.codebooks, l.gemm_scales, y) for n, l, y in zip(Ns, layers, ys)]
+    for rep in range(2):                                     # the second call reuses the workspace as the first left it
+        cg.codegemm_gemm_grouped(desc, plan, layers[0].x, members, ws.t, ws_bytes, stream())
+        torch.cuda.synchronize()
+        assert ws.intact(), "bytes outside the grouped workspace were written"
+        for l, y, inp in zip(layers, ys, inps):
+            l.check_guards("grouped launch")
+            y_ref, T = oracle.gemm(x, inp.codes, inp.codebooks, inp.scales)
+            check_against_oracle(y.cpu().numpy(), y_ref, T, f"grouped member N={inp.case.N}")
+            alone = l.gemm()
+            torch.cuda.synchronize()
+            assert torch.equal(alone, y), f"member N={inp.case.N} differs from the single-layer call (call {rep})"
+    return plan
+
+
+@pytest.mark.parametrize("K,Ns,v,m,B,g", [
+    (1024, (512, 128, 128), 8, 2, 1, -1),          # q, k, v of a small block
+    (1024, (384, 384), 8, 2, 1, -1),               # gate and up
+    (1000, (200, 72, 136, 8), 8, 1, 1, -1),        # four members, ragged N and K
+    (2048, (640, 256), 4, 1, 2, -1),               # two batch rows
+    (1024, (520, 130, 130), 8, 2, 1, 128),         # group scales
+    (2048, (300, 300), 16, 3, 1, 32),
+    (512, (4096,), 8, 2, 1, -1),                   # a group of one
+])
+def test_grouped_small(K, Ns, v, m, B, g):
+    run_group(K, list(Ns), v, m, B, g)
+
+
+@pytest.mark.parametrize("waves,row_words,k_splits,psum", [(8, 1, 3, 0), (16, 1, 2, 0), (16, 2, 4, 0), (8, 2, 1, 0), (8, 1, 2, 1)])
+def test_grouped_plans(waves, row_words, k_splits, psum):
+    """Explicit plans: block heights of 128..512 rows, with and without a split of K, members whose
+    heights are not multiples of the block, fp16 Psumbook."""
+    plan = cg.Plan.make(waves, row_words, k_splits, 1, psum)
+    run_group(2048, [700, 130, 260], 8, 2, 1, -1, plan=plan, seed=7100 + waves + row_words)
+
+
+def test_grouped_fp32_output():
+    run_group(1024, [256, 384], 8, 2, 1, -1, y_fp32=True)
+
+
+@pytest.mark.parametrize("K,Ns,g", [(8192, (8192, 1024, 1024), -1), (8192, (28672, 28672), -1), (8192, (8192, 1024, 1024), 128)])
+def test_grouped_at_70b_decoder_block(K, Ns, g):
+    """The q/k/v and gate/up groups of the Llama-3-70B decoder block at full size, default plan of the summed height."""
+    run_group(K, list(Ns), 8, 2, 1, g, seed=7300)
+
+
+def test_grouped_rejects_bad_arguments():
+    desc = cg.Desc.make(1, 1024, 768, 8, 2)
+    plan = cg.codegemm_default_plan(desc)
+    assert cg.codegemm_grouped_workspace_bytes(desc, plan, [512, 128]) == 0            # sum != out_features
+    assert cg.codegemm_grouped_workspace_bytes(desc, plan, [512, 128, 64, 32, 32]) == 0  # five members
+    assert cg.codegemm_grouped_workspace_bytes(desc, plan, [512, 256]) > 0
+    d4 = cg.Desc.make(8, 1024, 768, 8, 2)
+    assert cg.codegemm_grouped_workspace_bytes(d4, cg.Plan.make(8, 1, 1, 4), [512, 256]) == 0   # batched-kernel plan
+    buf = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    with pytest.raises(cg.CodegemmError):
+        cg.codegemm_gemm_grouped(desc, plan, buf, [(512, buf, buf, buf, buf), (128, buf, buf, buf, buf)], buf, buf.numel(), stream())
+    with pytest.raises(cg.CodegemmError):                                                  # workspace too small
+        cg.codegemm_gemm_grouped(desc, plan, buf, [(512, buf, buf, buf, buf), (256, buf, buf, buf, buf)], buf, 64, stream())
+    with pytest.raises(cg.CodegemmError):                                                  # null member pointer
+        cg.codegemm_gemm_grouped(desc, plan, buf, [(512, buf, None, buf, buf), (256, buf, buf, buf, buf)], buf, buf.numel(), stream())
+    torch.cuda.synchronize()
