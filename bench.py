@@ -519,7 +519,7 @@ def main():
             out["config"]["decoder_block_us"] = round(decoder_block_us(torch, layers, order, args.launch), 3)
             log(f"decoder block, {len(order)} linears launched back to back (timed): {out['config']['decoder_block_us']:.2f} us; "
                 f"sum of the per-shape times: {out['config']['decoder_block_sum_us']:.2f} us")
-            if key in ("c2", "c3", "c7", "c8") and all(L.plan.batch_group != 4 for L in layers):
+            if key in ("c2", "c3", "c7", "c8"):
                 # the same seven layers as four launches: q, k and v grouped, o, gate and up grouped, down
                 gorder = [Group(cg, torch, [(layers[0], 0), (layers[1], 0), (layers[1], 1)]), 0,
                           Group(cg, torch, [(layers[2], 0), (layers[2], 1)]), 3]

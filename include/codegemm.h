@@ -222,15 +222,14 @@ int codegemm_gemm(const codegemm_desc *desc, const codegemm_plan *plan,
  *   desc->out_features   the SUM of the members' out_features (checked);
  *   plan                 required (not NULL): codegemm_default_plan(desc) suits,
  *                        since the launch fills the chip like one layer of the
- *                        summed height; batch_group must be 1 or 2 (so batch <= 2
- *                        under default plans), batch <= 32;
+ *                        summed height; batch <= 32;
  *   group[i]             device pointers as for codegemm_gemm, y [batch][out_features_i];
  *   workspace            codegemm_grouped_workspace_bytes() bytes, initialised once
  *                        with codegemm_workspace_init; any workspace may be shared
  *                        between grouped and plain calls on one stream.
  * Errors: CODEGEMM_INVALID_ARG (count outside 1..4, null or misaligned pointer,
- * out_features not summing to desc->out_features), CODEGEMM_UNSUPPORTED (batched
- * kernel plan, batch > 32, more than 65535 row blocks), CODEGEMM_WORKSPACE_TOO_SMALL.
+ * out_features not summing to desc->out_features), CODEGEMM_UNSUPPORTED (batch > 32,
+ * more than 65535 row blocks), CODEGEMM_WORKSPACE_TOO_SMALL.
  * codegemm_grouped_workspace_bytes returns 0 on any of the former two.
  */
 typedef struct codegemm_group_member {

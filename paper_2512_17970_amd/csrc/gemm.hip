@@ -211,8 +211,7 @@ extern "C" int codegemm_gemm_static(const codegemm_desc* desc, const codegemm_pl
 // ---- several layers that share x in one launch ----------------------------------------------
 
 // Geometry of the members of a group under one plan, and the geometry of the whole launch (row
-// blocks summed).  The plan has to suit every member, batch rows go through the gather kernel
-// that handles one or two of them per pass, and a launch takes at most kBatchPerLaunch rows.
+// blocks summed).  The plan has to suit every member, and a launch takes at most kBatchPerLaunch rows.
 static int group_geometry(const codegemm_desc* desc, const codegemm_plan* plan, const int32_t* out_features,
                           int count, Geometry* members, Geometry* whole)
 {
@@ -228,7 +227,6 @@ static int group_geometry(const codegemm_desc* desc, const codegemm_plan* plan, 
         total += out_features[i];
     }
     if (total != desc->out_features) return CODEGEMM_INVALID_ARG;
-    if (members[0].BG == 4) return CODEGEMM_UNSUPPORTED;
     *whole = members[0];
     whole->N = (int)total;
     whole->NBLK = 0; whole->NGR = 0; whole->Npad = 0;

@@ -75,8 +75,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be: keeps buffer descriptors in scalar registers
     const int ks = blockIdx.x;
-    const Member mm = p.mem[0];                        // batched launches hold one layer
-    const int blk = blockIdx.y;                        // row block of GPW granules
+    const Member mm = member_of(p, blockIdx.y);        // the layer this workgroup works for
+    const int blk = blockIdx.y - mm.blk0;              // its row block of GPW granules
     const int b0 = blockIdx.z * BG;
     const int kt0 = ks * p.KPW;
     const int nq = min(p.KPW, p.NKT - kt0);            // units of this workgroup (>= 1 by construction)

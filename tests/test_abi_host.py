@@ -212,7 +212,8 @@ def test_grouped_launch_host_validation():
     assert cg.codegemm_grouped_workspace_bytes(d, plan, [8192, 1024]) == 0              # heights do not add up
     assert cg.codegemm_grouped_workspace_bytes(d, plan, [8192, 1024, 512, 256, 256]) == 0   # more than four layers
     assert cg.codegemm_grouped_workspace_bytes(d, plan, [10240, 0]) == 0                # an empty layer
-    assert cg.codegemm_grouped_workspace_bytes(d, cg.Plan.make(8, 1, 1, 4), Ns) == 0    # batched-kernel plan
+    d8 = cg.Desc.make(8, 8192, 10240, 8, 2)
+    assert cg.codegemm_grouped_workspace_bytes(d8, cg.Plan.make(8, 1, 2, 4), Ns) == 65536 + 8 * 2 * pad * 4   # batched-kernel plan
     d64 = cg.Desc.make(64, 8192, 10240, 8, 2)
     assert cg.codegemm_grouped_workspace_bytes(d64, cg.Plan.make(8, 1, 1, 1), Ns) == 0  # more rows than one launch takes
     # ragged members are padded one by one

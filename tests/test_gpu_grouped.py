@@ -67,6 +67,19 @@ def test_grouped_plans(waves, row_words, k_splits, psum):
     run_group(2048, [700, 130, 260], 8, 2, 1, -1, plan=plan, seed=7100 + waves + row_words)
 
 
+@pytest.mark.parametrize("K,Ns,v,m,B,g,plan", [
+    (1024, (512, 200, 130), 8, 2, 4, -1, None),
+    (2048, (700, 260), 8, 2, 7, -1, (8, 1, 3, 4)),         # ragged batch group, K split
+    (1024, (1100, 1030), 8, 2, 8, -1, (16, 2, 2, 4)),      # 1024-row blocks
+    (2048, (300, 520, 8), 4, 1, 32, 128, None),            # group scales, a full launch of batch rows
+    (1024, (384, 384), 16, 3, 5, -1, None),
+])
+def test_grouped_batched_kernel(K, Ns, v, m, B, g, plan):
+    """Groups through the batched kernel (4 batch rows per pass)."""
+    pl = run_group(K, list(Ns), v, m, B, g, plan=None if plan is None else cg.Plan.make(*plan), seed=7200 + B)
+    assert pl.batch_group == 4, pl
+
+
 def test_grouped_fp32_output():
     run_group(1024, [256, 384], 8, 2, 1, -1, y_fp32=True)
 
@@ -83,8 +96,8 @@ def test_grouped_rejects_bad_arguments():
     assert cg.codegemm_grouped_workspace_bytes(desc, plan, [512, 128]) == 0            # sum != out_features
     assert cg.codegemm_grouped_workspace_bytes(desc, plan, [512, 128, 64, 32, 32]) == 0  # five members
     assert cg.codegemm_grouped_workspace_bytes(desc, plan, [512, 256]) > 0
-    d4 = cg.Desc.make(8, 1024, 768, 8, 2)
-    assert cg.codegemm_grouped_workspace_bytes(d4, cg.Plan.make(8, 1, 1, 4), [512, 256]) == 0   # batched-kernel plan
+    d64 = cg.Desc.make(64, 1024, 768, 8, 2)
+    assert cg.codegemm_grouped_workspace_bytes(d64, cg.Plan.make(8, 1, 1, 4), [512, 256]) == 0   # more rows than one launch takes
     buf = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
     with pytest.raises(cg.CodegemmError):
         cg.codegemm_gemm_grouped(desc, plan, buf, [(512, buf, buf, buf, buf), (128, buf, buf, buf, buf)], buf, buf.numel(), stream())
