@@ -220,9 +220,9 @@ int codegemm_gemm(const codegemm_desc *desc, const codegemm_plan *plan,
  * Member i's result is bit-identical to codegemm_gemm on that layer alone with
  * the same plan.
  *   desc->out_features   the SUM of the members' out_features (checked);
- *   plan                 required (not NULL): codegemm_default_plan(desc) suits,
- *                        since the launch fills the chip like one layer of the
- *                        summed height; batch <= 32;
+ *   plan                 applies to every member; NULL = codegemm_default_plan(desc),
+ *                        which suits since the launch fills the chip like one
+ *                        layer of the summed height; batch <= 32;
  *   group[i]             device pointers as for codegemm_gemm, y [batch][out_features_i];
  *   workspace            codegemm_grouped_workspace_bytes() bytes, initialised once
  *                        with codegemm_workspace_init; any workspace may be shared

@@ -215,9 +215,15 @@ extern "C" int codegemm_gemm_static(const codegemm_desc* desc, const codegemm_pl
 static int group_geometry(const codegemm_desc* desc, const codegemm_plan* plan, const int32_t* out_features,
                           int count, Geometry* members, Geometry* whole)
 {
-    if (!desc || !plan || !out_features) return CODEGEMM_INVALID_ARG;
+    if (!desc || !out_features) return CODEGEMM_INVALID_ARG;
     if (count < 1 || count > kMaxGroup) return CODEGEMM_INVALID_ARG;
     if (desc->batch > kBatchPerLaunch) return CODEGEMM_UNSUPPORTED;
+    codegemm_plan of_sum;
+    if (!plan) {   // the default plan of one layer of the summed height, for every member
+        const int st = codegemm_default_plan(desc, &of_sum);
+        if (st) return st;
+        plan = &of_sum;
+    }
     long long total = 0;
     for (int i = 0; i < count; ++i) {
         codegemm_desc d = *desc;

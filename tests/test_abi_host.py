@@ -209,6 +209,7 @@ def test_grouped_launch_host_validation():
     # counter area + one fp32 partial per K range and padded row, member by member
     pad = sum(-(-n // 128) * 128 for n in Ns)
     assert ws == 65536 + plan.k_splits * pad * 4
+    assert cg.codegemm_grouped_workspace_bytes(d, None, Ns) == ws                       # NULL plan = default plan of the sum
     assert cg.codegemm_grouped_workspace_bytes(d, plan, [8192, 1024]) == 0              # heights do not add up
     assert cg.codegemm_grouped_workspace_bytes(d, plan, [8192, 1024, 512, 256, 256]) == 0   # more than four layers
     assert cg.codegemm_grouped_workspace_bytes(d, plan, [10240, 0]) == 0                # an empty layer

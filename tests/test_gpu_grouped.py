@@ -80,6 +80,33 @@ def test_grouped_batched_kernel(K, Ns, v, m, B, g, plan):
     assert pl.batch_group == 4, pl
 
 
+def test_grouped_null_plan_is_the_default_plan_of_the_sum():
+    K, Ns = 2048, [900, 300, 300]
+    desc = cg.Desc.make(1, K, sum(Ns), 8, 2)
+    plan = cg.codegemm_default_plan(desc)
+    inps = [synth.generate(synth.custom_case(K, n, 8, 2, 1, seed=7400 + i)) for i, n in enumerate(Ns)]
+    layers = []
+    for inp in inps:
+        inp.x = inps[0].x
+        layers.append(DeviceLayer(inp, plan=plan))
+    ws_bytes = cg.codegemm_grouped_workspace_bytes(desc, None, Ns)
+    assert ws_bytes == cg.codegemm_grouped_workspace_bytes(desc, plan, Ns) > 0
+    ws = Guarded(ws_bytes)
+    cg.codegemm_workspace_init(ws.t, ws_bytes, stream())
+    out = {}
+    for which in (None, plan):
+        ys = [l.new_y() for l in layers]
+        cg.codegemm_gemm_grouped(desc, which, layers[0].x, [(n, l.packed, l.codebooks, l.gemm_scales, y) for n, l, y in zip(Ns, layers, ys)],
+                                 ws.t, ws_bytes, stream())
+        torch.cuda.synchronize()
+        out[which is None] = ys
+    for a, b_, inp in zip(out[True], out[False], inps):
+        assert torch.equal(a, b_)
+        y_ref, T = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+        check_against_oracle(a.cpu().numpy(), y_ref, T, "grouped, NULL plan")
+    assert ws.intact()
+
+
 def test_grouped_fp32_output():
     run_group(1024, [256, 384], 8, 2, 1, -1, y_fp32=True)
 
