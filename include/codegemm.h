@@ -21,8 +21,10 @@
  *   - The caller owns every buffer.  The library allocates no device memory
  *     and never synchronises: work is enqueued on `stream` (a hipStream_t
  *     passed as void*; NULL = the default stream).  The only state it keeps
- *     between calls is a per-process, mutex-guarded note of which kernels have
- *     had their LDS limit raised on which device (a one-time HIP attribute).
+ *     between calls is per-process and mutex-guarded: a note of which kernels
+ *     have had their LDS limit raised on which device (a one-time HIP
+ *     attribute), and, once codegemm_gemm_static has been used on a device, the
+ *     address of that device's copy of the library's static workspace.
  *   - Inputs are read-only.  Outputs are fully overwritten.  Buffers must not
  *     alias.  Every pointer must be 16-byte aligned.
  *   - Return value: CODEGEMM_OK (0) or a negative codegemm_status.  No entry
