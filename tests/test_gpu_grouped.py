@@ -107,6 +107,62 @@ def test_grouped_null_plan_is_the_default_plan_of_the_sum():
     assert ws.intact()
 
 
+def test_grouped_launch_replays_from_a_hip_graph():
+    """The grouped call only launches a kernel, so it can be captured; every replay gives the eager bits,
+    with eager grouped and single-layer calls on the same workspace between the replays."""
+    K, Ns = 2048, [700, 260, 130]
+    desc = cg.Desc.make(1, K, sum(Ns), 8, 2)
+    plan = cg.Plan.make(8, 2, 4, 1)
+    inps = [synth.generate(synth.custom_case(K, n, 8, 2, 1, seed=7500 + i)) for i, n in enumerate(Ns)]
+    layers = []
+    for inp in inps:
+        inp.x = inps[0].x
+        layers.append(DeviceLayer(inp, plan=plan))
+    ws_bytes = max(cg.codegemm_grouped_workspace_bytes(desc, plan, Ns), max(l.ws_bytes for l in layers))
+    ws = Guarded(ws_bytes)
+    cg.codegemm_workspace_init(ws.t, ws_bytes, stream())
+
+    def call(ys):
+        cg.codegemm_gemm_grouped(desc, plan, layers[0].x, [(n, l.packed, l.codebooks, l.gemm_scales, y) for n, l, y in zip(Ns, layers, ys)],
+                                 ws.t, ws_bytes, stream())
+
+    eager = [l.new_y() for l in layers]
+    call(eager)
+    torch.cuda.synchronize()
+    for y, inp in zip(eager, inps):
+        y_ref, T = oracle.gemm(inp.x, inp.codes, inp.codebooks, inp.scales)
+        check_against_oracle(y.cpu().numpy(), y_ref, T, "grouped, eager")
+    outs = [[torch.full_like(y, float("nan")) for y in eager] for _ in range(2)]
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            for ys in outs:
+                call(ys)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for ys in outs:
+            for y in ys:
+                y.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        assert ws.intact()
+        for ys in outs:
+            for y, e in zip(ys, eager):
+                assert torch.equal(y, e), f"replay {rep} differs from the eager grouped call"
+        # eager work on the same workspace between the replays: a single layer, then the group again
+        l = layers[rep % len(layers)]
+        z = l.new_y()
+        cg.codegemm_gemm(l.desc, plan, l.x, l.packed, l.codebooks, l.gemm_scales, z, ws.t, ws_bytes, stream())
+        again = [torch.full_like(y, float("nan")) for y in eager]
+        call(again)
+        torch.cuda.synchronize()
+        assert torch.equal(z, eager[rep % len(layers)])
+        for y, e in zip(again, eager):
+            assert torch.equal(y, e)
+
+
 def test_grouped_fp32_output():
     run_group(1024, [256, 384], 8, 2, 1, -1, y_fp32=True)
 
