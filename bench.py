@@ -78,8 +78,9 @@ class Layer:
         self.plan = plan_override if plan_override is not None else cg.codegemm_default_plan(self.desc)
         if psum_fp16 and plan_override is None:
             p = self.plan
-            rw = 1 if (case.g > 0 and p.waves == 16) else min(p.row_words, 2)
-            self.plan = cg.Plan.make(p.waves, rw, p.k_splits, 1, 1)
+            waves = 16 if p.waves == 14 else p.waves     # the fp16 Psumbook pairs up 8 or 16 wavefronts
+            rw = 1 if (case.g > 0 and waves == 16) else min(p.row_words, 2)
+            self.plan = cg.Plan.make(waves, rw, p.k_splits, 1, 1)
         dev = lambda a: torch.from_numpy(a).cuda()
         self.x, self.codes = dev(inp.x), dev(inp.codes)
         self.codebooks, self.scales = dev(inp.codebooks), dev(inp.scales)
@@ -376,9 +377,9 @@ def sweep_report(torch, cg, synth, cases, launch):
         ngr, nkt = -(-case.N // 128), -(-case.J // 32)
         groups = -(-case.B // bg) if bg == 4 else 1
         res = []
-        for waves, rw in [(8, 1), (16, 1), (8, 2), (16, 2), (16, 4), (8, 4)]:
-            gpw = rw * waves // (4 if bg == 4 else 8)
-            nblk = -(-ngr // gpw) * groups
+        for waves, rw in [(8, 1), (16, 1), (8, 2), (16, 2), (14, 2), (16, 4), (8, 4)]:
+            rows = rw * waves * (32 if bg == 4 else 16)                   # rows of one workgroup
+            nblk = -(-ngr * 128 // rows) * groups
             cands = set()
             for target in (128, 192, 224, 256, 384, 512):
                 ks = max(1, min(nkt, target // nblk))

@@ -83,7 +83,9 @@ typedef struct codegemm_desc {
  * buffered for m <= 2) once per unit.
  */
 typedef struct codegemm_plan {
-    int32_t waves;          /* wavefronts per workgroup: 8 or 16                                      */
+    int32_t waves;          /* wavefronts per workgroup: 8, 14 or 16 (14: row_words = 2, batch_group  */
+                            /* 1 or 2, fp32 Psumbook; its 448-row blocks divide heights of 7 * 2^k    */
+                            /* rows into a number of workgroups that fills 256 compute units)         */
     int32_t row_words;      /* 8-row code words per lane per unit: 1, 2 or 4.  The workgroup owns     */
                             /* 16 * waves * row_words rows (32 * waves * row_words when batch_group   */
                             /* = 4).  Limits (registers): batch_group 1 or 2: row_words = 2 needs     */

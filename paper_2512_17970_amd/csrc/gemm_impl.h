@@ -498,7 +498,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
 {
     constexpr int NTILES = 8 * M;                      // 32x32 MFMA blocks in one Psumbook
     constexpr int TPW = PH ? 1 : (NTILES + NW - 1) / NW;   // blocks per wavefront (fp32 Psumbook)
-    constexpr int GPW = RPL * NW / 8;                  // 128-row granules per workgroup
+    constexpr int PIECES = RPL * NW;                   // 16-row pieces (one row word of one wavefront) per workgroup
     typedef PsumLayout<M> L;
     typedef PsumLayoutH<M> LH;
     constexpr int NBUF = PH ? 2 : L::kBuffers;
@@ -509,7 +509,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
     constexpr int WPP = NPAIR >= NW ? 1 : NW / NPAIR;  // wavefronts per pair (1 or 2)
     static_assert(!PH || (NPAIR % NW == 0 || NW % NPAIR == 0), "pairs and wavefronts divide");
     static_assert(!PH || WPP <= 2, "at most two wavefronts per pair");
-    static_assert(NW == 8 || NW == 16, "8 or 16 wavefronts");
+    static_assert(NW == 8 || NW == 14 || NW == 16, "8, 14 or 16 wavefronts");
+    static_assert(!PH || NW != 14, "the fp16 Psumbook pairs up 8 or 16 wavefronts");
     static_assert((D & 1) == 0, "ring depth must be even (buffer parity is compile-time)");
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -521,7 +522,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be: keeps buffer descriptors in scalar registers
     const int ks = blockIdx.x;
     const Member mm = member_of(p, blockIdx.y);        // the layer this workgroup works for
-    const int blk = blockIdx.y - mm.blk0;              // its row block of GPW granules
+    const int blk = blockIdx.y - mm.blk0;              // its row block of PIECES x 16 rows
     const int b0 = blockIdx.z * BG;
     const int kt0 = ks * p.KPW;
     const int nq = min(p.KPW, p.NKT - kt0);            // units of this workgroup (>= 1 by construction)
@@ -584,10 +585,15 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
         }
     };
     // Codes of unit u for this lane: RPL words of 8*M bytes (8 rows x M codebooks at one slot).
-    // Word q (q < RPL) of this wavefront belongs to granule blk*GPW + q*(NW/8) + wave/8.
+    // Word q (q < RPL) of this wavefront is piece blk*PIECES + q*NW + wave of the matrix: rows
+    // 16*piece .. 16*piece+15, i.e. row-lanes 2*(piece%8), +1 of granule piece/8.  With 8 or 16
+    // wavefronts piece%8 = wave%8 for every q; with 14 it differs from word to word.
     constexpr int kUnitBytes = 128 * 32 * M;
-    auto granule_of = [&](int q) -> int { return blk * GPW + q * (NW / 8) + wave / 8; };
-    const int entry = (wave % 8) * kWave + lane;       // (row-lane, slot) index inside the unit
+    auto piece_of = [&](int q) -> int { return blk * PIECES + q * NW + wave; };
+    auto granule_of = [&](int q) -> int { return piece_of(q) >> 3; };
+    int entry[RPL];                                    // (row-lane, slot) index inside the unit
+#pragma unroll
+    for (int q = 0; q < RPL; ++q) entry[q] = (piece_of(q) & 7) * kWave + lane;
     __amdgpu_buffer_rsrc_t c_rsrc[RPL];
 #pragma unroll
     for (int q = 0; q < RPL; ++q) {
@@ -602,11 +608,11 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
 #pragma unroll
             for (int part = 0; part < (M + 1) / 2; ++part) {
                 if (2 * part + 1 == M) {
-                    const u32x2_t t = __builtin_amdgcn_raw_buffer_load_b64(c_rsrc[q], u * kUnitBytes + part * 8192 + entry * 8, 0, 2);
+                    const u32x2_t t = __builtin_amdgcn_raw_buffer_load_b64(c_rsrc[q], u * kUnitBytes + part * 8192 + entry[q] * 8, 0, 2);
                     dst[q][4 * part + 0] = t.x;
                     dst[q][4 * part + 1] = t.y;
                 } else {
-                    const u32x4_t t = __builtin_amdgcn_raw_buffer_load_b128(c_rsrc[q], u * kUnitBytes + part * 8192 + entry * 16, 0, 2);
+                    const u32x4_t t = __builtin_amdgcn_raw_buffer_load_b128(c_rsrc[q], u * kUnitBytes + part * 8192 + entry[q] * 16, 0, 2);
                     dst[q][4 * part + 0] = t.x;
                     dst[q][4 * part + 1] = t.y;
                     dst[q][4 * part + 2] = t.z;
@@ -620,7 +626,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
     // ring of their own, two units deep.
     constexpr int DS = 2;
     __amdgpu_buffer_rsrc_t s_rsrc[GS ? RPL : 1];
-    int s_off = 0;
+    int s_off[GS ? RPL : 1] = {};
     if constexpr (GS) {
 #pragma unroll
         for (int q = 0; q < RPL; ++q) {
@@ -628,12 +634,14 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
             const uint8_t* base = mm.gscales + ((size_t)min(gr, mm.NGR - 1) * p.NKT + kt0) * p.GPU * 256;
             s_rsrc[q] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, gr < mm.NGR ? nq * p.GPU * 256 : 0, kRsrcFlags);
         }
-        s_off = ((lane & 31) >> p.gshift) * 256 + ((wave % 8) * 2 + khalf) * 16;
+#pragma unroll
+        for (int q = 0; q < RPL; ++q)
+            s_off[q] = ((lane & 31) >> p.gshift) * 256 + ((piece_of(q) & 7) * 2 + khalf) * 16;
     }
     auto load_scales = [&](half8_t (&dst)[RPL], int u) {
 #pragma unroll
         for (int q = 0; q < RPL; ++q)
-            dst[q] = __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(s_rsrc[GS ? q : 0], u * p.GPU * 256 + s_off, 0, 0));
+            dst[q] = __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(s_rsrc[GS ? q : 0], u * p.GPU * 256 + s_off[GS ? q : 0], 0, 0));
     };
 #if CODEGEMM_ABLATE & 4
     bool first_build = true;
@@ -815,7 +823,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
     // (the Psumbook is no longer needed), indexed by the row's position inside the
     // workgroup's block, so that the global stores and loads below are coalesced over all
     // threads.
-    constexpr int ROWS = GPW * kGranuleRows;                          // rows of this workgroup's block
+    constexpr int ROWS = PIECES * 16;                                 // rows of this workgroup's block
     float* stage = planes;                                           // [BG][ROWS]
     {
         constexpr int NV = (RPL == 1) ? 8 : 16;                      // values reduced together
@@ -823,7 +831,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
 #pragma unroll
         for (int q0 = 0; q0 < RPL; q0 += NV / 8) {
             const int q = q0 + idx / 8;
-            const int local = (q * (NW / 8) + wave / 8) * kGranuleRows + ((wave % 8) * 2 + khalf) * kRowsPerLane + idx % 8;
+            const int local = (q * NW + wave) * 16 + khalf * kRowsPerLane + idx % 8;   // piece, half-wavefront, row
 #pragma unroll
             for (int bb = 0; bb < BG; ++bb) {
                 float v[NV];
@@ -865,6 +873,9 @@ int launch_gemm_mvb(const Geometry& g, const GemmParams& p, hipStream_t stream)
     if (g.NW == 16 && g.RPL == 1) return launch_gemm_one<M, V, 16, 1, BG, 2, GS>(g, p, stream);
     if constexpr (BG * M <= 4) {
         if (g.NW == 16 && g.RPL == 2) return launch_gemm_one<M, V, 16, 2, BG, 2, GS>(g, p, stream);
+        // 448-row blocks: matrices whose height is 7 * 2^k (the Llama up/gate projections) then
+        // divide into a number of workgroups that fills 256 compute units
+        if (g.NW == 14 && g.RPL == 2) return launch_gemm_one<M, V, 14, 2, BG, 2, GS>(g, p, stream);
     }
     if constexpr (BG * M <= 8) {   // 8 wavefronts have twice the registers per lane
         if (g.NW == 8 && g.RPL == 2) return launch_gemm_one<M, V, 8, 2, BG, 2, GS>(g, p, stream);

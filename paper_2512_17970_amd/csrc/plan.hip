@@ -28,7 +28,11 @@ static int validate_desc(const codegemm_desc* d)
 
 static int validate_plan(const codegemm_desc* d, const codegemm_plan* p)
 {
-    if (p->waves != 8 && p->waves != 16) return CODEGEMM_UNSUPPORTED;
+    if (p->waves != 8 && p->waves != 14 && p->waves != 16) return CODEGEMM_UNSUPPORTED;
+    if (p->waves == 14) {
+        // 448-row blocks: gather kernel for one or two batch rows only, fp32 Psumbook, registers as for 16 wavefronts
+        if (p->row_words != 2 || p->batch_group > 2 || p->psum_dtype != CODEGEMM_PSUM_FP32) return CODEGEMM_UNSUPPORTED;
+    }
     if (p->row_words != 1 && p->row_words != 2 && p->row_words != 4) return CODEGEMM_UNSUPPORTED;
     if (p->row_words == 4 && p->waves != 16 && p->batch_group != 4) return CODEGEMM_UNSUPPORTED;
     if (p->k_splits < 1) return CODEGEMM_UNSUPPORTED;
@@ -128,7 +132,7 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
     // unit).  When K is too short for that with 2 row words, blocks of half the height double
     // the workgroups (plan sweeps: 1024-output shapes -0.3 us).
     auto ranges = [&](int row_words, int* workgroups) {
-        const int nblk = ceil_div(ngr, row_words * p->waves / 8);
+        const int nblk = ceil_div(ngr * kGranuleRows, row_words * p->waves * 16);
         int nks = 256 / nblk;
         if (nks > nkt) nks = nkt;
         if (nks < 1) nks = 1;
@@ -138,6 +142,19 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
     };
     int wgs = 0;
     p->k_splits = ranges(p->row_words, &wgs);
+    if (p->waves == 16 && p->row_words == 2) {
+        // 448-row blocks (14 wavefronts) when they fill more of the 256 compute units: heights of
+        // 7 * 2^k rows (the Llama up/gate projections) divide into 224 workgroups of 512 rows but
+        // into 256 of 448 (8192->28672: 7 % more of the chip streams, -0.5 us)
+        p->waves = 14;
+        int wgs14 = 0;
+        const int nks14 = ranges(2, &wgs14);
+        if (wgs14 > wgs && wgs >= 192) {
+            p->k_splits = nks14;
+            return;
+        }
+        p->waves = 16;
+    }
     if (p->row_words == 2 && wgs <= 128) {
         int wgs1 = 0;
         const int nks1 = ranges(1, &wgs1);
@@ -170,7 +187,8 @@ int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g
     g->BG = plan->batch_group;
     g->psum_fp16 = plan->psum_dtype == CODEGEMM_PSUM_FP16;
     g->NGR = ceil_div(g->N, kGranuleRows);
-    g->NBLK = ceil_div(g->NGR, g->RPL * g->NW / (g->BG == 4 ? 4 : 8));
+    // rows per workgroup: 16 per wavefront and row word (32 in the batched kernel)
+    g->NBLK = ceil_div(g->NGR * kGranuleRows, g->RPL * g->NW * (g->BG == 4 ? 32 : 16));
     g->NKT = ceil_div(g->J, kSlots);
     int nks = plan->k_splits < g->NKT ? plan->k_splits : g->NKT;
     g->KPW = ceil_div(g->NKT, nks);

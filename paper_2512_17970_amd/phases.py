@@ -40,8 +40,8 @@ def workgroups(desc: binding.Desc, plan: binding.Plan) -> int:
     """Workgroups of one batch group under `plan` (row blocks x K ranges)."""
     J = desc.in_features // desc.vec_len
     ngr, nkt = -(-desc.out_features // 128), -(-J // 32)
-    gpw = plan.row_words * plan.waves // (4 if plan.batch_group == 4 else 8)
-    nblk = -(-ngr // gpw)
+    rows = plan.row_words * plan.waves * (32 if plan.batch_group == 4 else 16)     # rows of one workgroup
+    nblk = -(-ngr * 128 // rows)
     nks = min(plan.k_splits, nkt)
     kpw = -(-nkt // nks)
     return nblk * -(-nkt // kpw)

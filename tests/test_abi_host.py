@@ -108,12 +108,12 @@ def test_default_plans_are_valid_for_all_workloads():
         for c in cases:
             d = cg.Desc.make(c.B, c.K, c.N, c.v, c.m)
             p = cg.codegemm_default_plan(d)
-            assert p.waves in (8, 16) and p.batch_group in (1, 2, 4)
+            assert p.waves in (8, 14, 16) and p.batch_group in (1, 2, 4)
             ngr = -(-c.N // 128)
             nkt = -(-c.J // 32)
             assert p.row_words in (1, 2, 4)
-            gpw = p.row_words * p.waves // (4 if p.batch_group == 4 else 8)      # granules per workgroup
-            nblk = -(-ngr // gpw) * (-(-c.B // p.batch_group) if p.batch_group == 4 else 1)
+            rows = p.row_words * p.waves * (32 if p.batch_group == 4 else 16)    # rows per workgroup
+            nblk = -(-ngr * 128 // rows) * (-(-c.B // p.batch_group) if p.batch_group == 4 else 1)
             assert 1 <= p.k_splits <= nkt and nblk * p.k_splits <= max(256, nblk)
             assert cg.codegemm_packed_codes_bytes(d) == ngr * 128 * nkt * 32 * c.m
             assert cg.codegemm_workspace_bytes(d) >= c.B * p.k_splits * ngr * 128 * 4
@@ -221,3 +221,19 @@ def test_grouped_launch_host_validation():
     d2 = cg.Desc.make(2, 1024, 130 + 129, 8, 2)
     p2 = cg.Plan.make(8, 1, 2, 2)
     assert cg.codegemm_grouped_workspace_bytes(d2, p2, [130, 129]) == 65536 + 2 * 2 * 512 * 4
+
+
+def test_448_row_blocks_in_plans():
+    """Heights of 7 * 2^k rows get 14-wavefront workgroups by default where those fill more compute units."""
+    p = cg.codegemm_default_plan(cg.Desc.make(1, 8192, 28672, 8, 2))
+    assert (p.waves, p.row_words, p.k_splits) == (14, 2, 4)                 # 64 blocks x 4 K ranges = 256 workgroups
+    p = cg.codegemm_default_plan(cg.Desc.make(1, 28672, 8192, 8, 2))
+    assert (p.waves, p.row_words, p.k_splits) == (16, 2, 16)                # 16 x 16 = 256 already
+    d = cg.Desc.make(1, 2048, 1000, 8, 2)
+    assert cg.codegemm_workspace_bytes(d, cg.Plan.make(14, 2, 2, 1)) > 0
+    assert cg.codegemm_workspace_bytes(d, cg.Plan.make(14, 1, 2, 1)) == 0   # only with two row words
+    assert cg.codegemm_workspace_bytes(d, cg.Plan.make(14, 2, 2, 1, binding.PSUM_FP16)) == 0
+    assert cg.codegemm_workspace_bytes(cg.Desc.make(8, 2048, 1000, 8, 2), cg.Plan.make(14, 2, 2, 4)) == 0
+    assert cg.codegemm_workspace_bytes(cg.Desc.make(1, 2048, 1000, 8, 3), cg.Plan.make(14, 2, 2, 2)) == 0   # registers
+    from paper_2512_17970_amd import phases
+    assert phases.workgroups(cg.Desc.make(1, 8192, 28672, 8, 2), cg.Plan.make(14, 2, 4, 1)) == 256

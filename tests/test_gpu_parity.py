@@ -56,6 +56,8 @@ def test_tiny_config(y_fp32):
 
 
 def plan_ok(waves, row_words, m, bg=1):
+    if waves == 14:                               # 448-row blocks: gather kernel for one or two batch rows
+        return row_words == 2 and bg <= 2 and bg * m <= 4
     if bg == 4:                                   # the batched kernel
         return row_words <= 2 or waves == 8
     if row_words == 4:
@@ -65,7 +67,7 @@ def plan_ok(waves, row_words, m, bg=1):
     return True
 
 
-@pytest.mark.parametrize("waves,row_words", [(8, 1), (16, 1), (8, 2), (16, 2), (16, 4)])
+@pytest.mark.parametrize("waves,row_words", [(8, 1), (16, 1), (8, 2), (16, 2), (16, 4), (14, 2)])
 @pytest.mark.parametrize("k_splits", [1, 3, 1000])
 @pytest.mark.parametrize("v,m", [(8, 2), (4, 1), (8, 1), (4, 2), (8, 3), (4, 4), (8, 4), (4, 3), (16, 4), (16, 3), (16, 1)])
 def test_every_plan_shape(v, m, k_splits, waves, row_words):
@@ -81,12 +83,22 @@ def test_every_plan_shape(v, m, k_splits, waves, row_words):
                                                           (8, 3, 8, 2, 1), (4, 3, 8, 1, 3), (8, 4, 16, 1, 2), (4, 4, 8, 2, 1),
                                                           (4, 2, 8, 2, 2), (8, 2, 16, 2, 2), (8, 2, 8, 4, 1), (4, 1, 8, 4, 2),
                                                           (8, 3, 16, 2, 1), (4, 4, 8, 4, 3), (16, 4, 16, 1, 2), (16, 3, 8, 2, 1),
-                                                          (16, 1, 16, 2, 2)])
+                                                          (16, 1, 16, 2, 2), (8, 2, 14, 2, 2), (4, 1, 14, 2, 1), (16, 2, 14, 2, 3)])
 def test_batch_groups(B, bg, v, m, waves, row_words, k_splits):
     if not plan_ok(waves, row_words, m, bg):
         pytest.skip("plan not offered for this m and batch group")
     case = synth.custom_case(v * 150, 1100, v, m, B, seed=98)
     run_case(case, plan=cg.Plan.make(waves, row_words, k_splits, bg), dequant=False)
+
+
+@pytest.mark.parametrize("N", [448, 449, 447, 896 + 16, 3 * 448 + 130, 1, 17, 5000])
+@pytest.mark.parametrize("v,m,g,B", [(8, 2, -1, 1), (8, 2, 128, 1), (4, 1, -1, 2), (8, 3, 32, 1), (16, 4, -1, 1)])
+def test_448_row_blocks(N, v, m, g, B):
+    """14-wavefront workgroups own 448 rows = 3.5 granules of the packed layout: row blocks that start and
+    end in the middle of a granule, with ragged last blocks on either side of a block and a granule boundary."""
+    unit = max(g, v * 32)
+    case = synth.custom_case(unit * 3 + (g if g > 0 else v * 5), N, v, m, B, seed=1400 + N, g=g)
+    run_case(case, plan=cg.Plan.make(14, 2, 2, B), dequant=False)
 
 
 def test_batched_kernel_long_ragged_k():
@@ -119,7 +131,7 @@ def test_group_scales_default_plan(K, N, v, m, B, g):
 
 
 @pytest.mark.parametrize("waves,row_words,bg", [(8, 1, 1), (16, 1, 1), (8, 2, 1), (16, 2, 1), (8, 2, 2), (16, 1, 2), (16, 2, 2),
-                                                (16, 1, 4), (8, 1, 4), (8, 2, 4), (16, 2, 4), (8, 4, 4)])
+                                                (16, 1, 4), (8, 1, 4), (8, 2, 4), (16, 2, 4), (8, 4, 4), (14, 2, 1), (14, 2, 2)])
 @pytest.mark.parametrize("k_splits", [1, 3])
 @pytest.mark.parametrize("v,m,g", [(8, 2, 128), (8, 2, 8), (4, 1, 32), (8, 3, 64), (4, 4, 16), (8, 1, 512)])
 def test_group_scales_every_plan_shape(v, m, g, k_splits, waves, row_words, bg):
@@ -388,7 +400,7 @@ def test_random_formats_shapes_and_plans():
         K = unit * int(rng.integers(1, max(2, 6000 // unit)))
         N = int(rng.integers(1, 1400))
         bg = 1 if B == 1 else int(rng.choice([1, 2, 4]))
-        plan = cg.Plan.make(int(rng.choice([8, 16])), int(rng.choice([1, 2, 4])), int(rng.choice([1, 2, 3, 5, 64])), bg)
+        plan = cg.Plan.make(int(rng.choice([8, 16, 14])), int(rng.choice([1, 2, 4])), int(rng.choice([1, 2, 3, 5, 64])), bg)
         desc = cg.Desc.make(B, K, N, v, m, g=g)
         if cg.codegemm_workspace_bytes(desc, plan) == 0:
             continue                                  # plan not offered for this format
