@@ -142,10 +142,12 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
     };
     int wgs = 0;
     p->k_splits = ranges(p->row_words, &wgs);
-    if (p->waves == 16 && p->row_words == 2) {
-        // 448-row blocks (14 wavefronts) when they fill more of the 256 compute units: heights of
-        // 7 * 2^k rows (the Llama up/gate projections) divide into 224 workgroups of 512 rows but
-        // into 256 of 448 (8192->28672: 7 % more of the chip streams, -0.5 us)
+    // 448-row blocks (14 wavefronts) when they fill more of the 256 compute units: heights of
+    // 7 * 2^k rows (the Llama up/gate projections) divide into 224 workgroups of 512 rows but
+    // into 256 of 448.  Measured at 8192->28672: -2 % to -5 % for one and three codebooks and with
+    // group scales; with two or four codebooks and one scale per row a tie or a loss (+0.1 us),
+    // because the 8m MFMA blocks of a Psumbook then divide evenly over 16 wavefronts and not over 14.
+    if (p->waves == 16 && p->row_words == 2 && ((m & 1) || d->group_size > 0)) {
         p->waves = 14;
         int wgs14 = 0;
         const int nks14 = ranges(2, &wgs14);

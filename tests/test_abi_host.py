@@ -225,8 +225,11 @@ def test_grouped_launch_host_validation():
 
 def test_448_row_blocks_in_plans():
     """Heights of 7 * 2^k rows get 14-wavefront workgroups by default where those fill more compute units."""
+    for m, g in ((1, -1), (3, -1), (2, 128)):
+        p = cg.codegemm_default_plan(cg.Desc.make(1, 8192, 28672, 8, m, g=g))
+        assert (p.waves, p.row_words, p.k_splits) == (14, 2, 4), (m, g)     # 64 blocks x 4 K ranges = 256 workgroups
     p = cg.codegemm_default_plan(cg.Desc.make(1, 8192, 28672, 8, 2))
-    assert (p.waves, p.row_words, p.k_splits) == (14, 2, 4)                 # 64 blocks x 4 K ranges = 256 workgroups
+    assert (p.waves, p.row_words, p.k_splits) == (16, 2, 4)                 # two codebooks, one scale per row: no gain measured
     p = cg.codegemm_default_plan(cg.Desc.make(1, 28672, 8192, 8, 2))
     assert (p.waves, p.row_words, p.k_splits) == (16, 2, 16)                # 16 x 16 = 256 already
     d = cg.Desc.make(1, 2048, 1000, 8, 2)
