@@ -59,7 +59,7 @@ def test_grouped_small(K, Ns, v, m, B, g):
     run_group(K, list(Ns), v, m, B, g)
 
 
-@pytest.mark.parametrize("waves,row_words,k_splits,psum", [(8, 1, 3, 0), (16, 1, 2, 0), (16, 2, 4, 0), (8, 2, 1, 0), (8, 1, 2, 1)])
+@pytest.mark.parametrize("waves,row_words,k_splits,psum", [(8, 1, 3, 0), (16, 1, 2, 0), (16, 2, 4, 0), (8, 2, 1, 0), (8, 1, 2, 1), (14, 2, 3, 0)])
 def test_grouped_plans(waves, row_words, k_splits, psum):
     """Explicit plans: block heights of 128..512 rows, with and without a split of K, members whose
     heights are not multiples of the block, fp16 Psumbook."""
@@ -167,7 +167,8 @@ def test_grouped_fp32_output():
     run_group(1024, [256, 384], 8, 2, 1, -1, y_fp32=True)
 
 
-@pytest.mark.parametrize("K,Ns,g", [(8192, (8192, 1024, 1024), -1), (8192, (28672, 28672), -1), (8192, (8192, 1024, 1024), 128)])
+@pytest.mark.parametrize("K,Ns,g", [(8192, (8192, 1024, 1024), -1), (8192, (28672, 28672), -1), (8192, (8192, 1024, 1024), 128),
+                                    (8192, (28672, 28672), 128)])
 def test_grouped_at_70b_decoder_block(K, Ns, g):
     """The q/k/v and gate/up groups of the Llama-3-70B decoder block at full size, default plan of the summed height."""
     run_group(K, list(Ns), 8, 2, 1, g, seed=7300)
