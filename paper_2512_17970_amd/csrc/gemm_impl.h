@@ -6,9 +6,11 @@
 //
 // Work decomposition.  A "unit" is 128 rows by 32 sub-vectors (32 * v weights along K);
 // its packed codes are contiguous in HBM, and so are the units of consecutive K tiles
-// of one 128-row granule.  One workgroup of NW wavefronts owns RPL * NW/8 granules and a
-// contiguous range of K tiles (all of K when k_splits = 1) and streams through them:
-//   * a half-wavefront (32 lanes) owns 8 rows in each of RPL granules; its lane s works
+// of one 128-row granule.  One workgroup of NW (8, 14 or 16) wavefronts owns 16 * NW * RPL
+// consecutive rows, i.e. RPL * NW/8 granules (3.5 of them with 14 wavefronts and RPL = 2:
+// rows are indexed by 16-row pieces of a granule), and a contiguous range of K tiles (all
+// of K when k_splits = 1), and streams through them:
+//   * a half-wavefront (32 lanes) owns RPL words of 8 rows; its lane s works
 //     on slot s of every K tile, so the 32 lanes always address 32 different slots = 32
 //     different LDS banks, whatever the code values are, and the 8 * RPL accumulators
 //     of a lane stay in registers for the whole range;
