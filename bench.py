@@ -377,8 +377,8 @@ def sweep_report(torch, cg, synth, cases, launch):
         ngr, nkt = -(-case.N // 128), -(-case.J // 32)
         groups = -(-case.B // bg) if bg == 4 else 1
         res = []
-        for waves, rw in [(8, 1), (16, 1), (8, 2), (16, 2), (14, 2), (16, 4), (8, 4)]:
-            rows = rw * waves * (32 if bg == 4 else 16)                   # rows of one workgroup
+        for waves, rw, bw in [(8, 1, 0), (16, 1, 0), (8, 2, 0), (16, 2, 0), (14, 2, 0), (16, 2, 2), (16, 4, 0), (8, 4, 0)]:
+            rows = rw * (waves - bw) * (32 if bg == 4 else 16)            # rows of one workgroup
             nblk = -(-ngr * 128 // rows) * groups
             cands = set()
             for target in (128, 192, 224, 256, 384, 512):
@@ -386,16 +386,16 @@ def sweep_report(torch, cg, synth, cases, launch):
                 cands.add(-(-nkt // -(-nkt // ks)))
             for ks in sorted(cands):
               for psum in ((0, 1) if bg == 1 else (0,)):                # Psumbook stored as fp32 / fp16
-                plan = cg.Plan.make(waves, rw, ks, bg, psum)
+                plan = cg.Plan.make(waves, rw, ks, bg, psum, bw)
                 if cg.codegemm_workspace_bytes(d, plan) == 0:
                     continue                                            # plan not offered for this format
                 L = Layer(cg, torch, synth, case, plan, copies_bytes=COLD_BYTES // 2)
                 call = graph_of(torch, L.gemm, 50).replay if launch == "graph" else (lambda L=L: [L.gemm() for _ in range(50)])
                 call(); call()
                 us = min(time_region(torch, call, 1) for _ in range(4)) * 1e3 / 50
-                res.append({"waves": waves, "row_words": rw, "k_splits": ks, "batch_group": bg, "psum_dtype": "fp16" if psum else "fp32",
+                res.append({"waves": waves, "row_words": rw, "k_splits": ks, "batch_group": bg, "psum_dtype": "fp16" if psum else "fp32", "build_waves": bw,
                             "workgroups": nblk * ks, "us_cold": us})
-                log(f"  {case.name} waves={waves} row_words={rw} k_splits={ks} psum={'fp16' if psum else 'fp32'} workgroups={nblk * ks}: {us:.2f} us")
+                log(f"  {case.name} waves={waves}{'(14+2)' if bw else ''} row_words={rw} k_splits={ks} psum={'fp16' if psum else 'fp32'} workgroups={nblk * ks}: {us:.2f} us")
                 del L
                 torch.cuda.empty_cache()
         res.sort(key=lambda r: r["us_cold"])

@@ -105,7 +105,11 @@ typedef struct codegemm_plan {
                             /* 3e-4 relative error to y; needs batch_group = 1, row_words <= 2, and with  */
                             /* group scales not (waves 16, row_words 2).                                 */
                             /* codegemm_default_plan never chooses it.                                    */
-    int32_t reserved[3];    /* must be zero */
+    int32_t build_waves;    /* 0: every wavefront builds its share of each Psumbook between two gathers.  */
+                            /* 2 (waves = 16, row_words = 2, batch_group = 1, fp32 Psumbook, m <= 2): the */
+                            /* last two wavefronts only build, one unit ahead; the other 14 stream,       */
+                            /* gather and own the workgroup's 448 rows                                    */
+    int32_t reserved[2];    /* must be zero */
 } codegemm_plan;
 
 enum {

@@ -50,14 +50,17 @@ class Desc(ctypes.Structure):
 class Plan(ctypes.Structure):
     """codegemm_plan"""
     _fields_ = [("waves", ctypes.c_int32), ("row_words", ctypes.c_int32), ("k_splits", ctypes.c_int32),
-                ("batch_group", ctypes.c_int32), ("psum_dtype", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
+                ("batch_group", ctypes.c_int32), ("psum_dtype", ctypes.c_int32), ("build_waves", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 2)]
 
     @classmethod
-    def make(cls, waves: int, row_words: int, k_splits: int, batch_group: int = 1, psum_dtype: int = 0):
-        return cls(waves, row_words, k_splits, batch_group, psum_dtype, (ctypes.c_int32 * 3)(0, 0, 0))
+    def make(cls, waves: int, row_words: int, k_splits: int, batch_group: int = 1, psum_dtype: int = 0, build_waves: int = 0):
+        return cls(waves, row_words, k_splits, batch_group, psum_dtype, build_waves, (ctypes.c_int32 * 2)(0, 0))
 
     def __repr__(self):
         tail = ", psum_dtype=fp16" if self.psum_dtype == PSUM_FP16 else ""
+        if self.build_waves:
+            tail += f", build_waves={self.build_waves}"
         return (f"Plan(waves={self.waves}, row_words={self.row_words}, k_splits={self.k_splits}, "
                 f"batch_group={self.batch_group}{tail})")
 

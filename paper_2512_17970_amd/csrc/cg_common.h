@@ -41,7 +41,8 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 struct Geometry {
     int B, K, N, v, m, J;
     int NW;         // wavefronts per workgroup (8 or 16; 14 in the kernel for one or two batch rows)
-    int RPL;        // 8-row words per lane per unit (1, 2 or 4): the workgroup owns 16 * NW * RPL rows
+    int NB;         // of the NW wavefronts, those that only build Psumbooks (0 or 2); the others own the rows
+    int RPL;        // 8-row words per lane per unit (1, 2 or 4): the workgroup owns 16 * (NW - NB) * RPL rows
                     // (32 * NW * RPL in the batched kernel, BG = 4)
     int BG;         // batch rows per pass over the codes
     int NGR;        // ceil(N / 128) granules

@@ -125,19 +125,10 @@ template <int V> struct Frag { typedef half4_t type; };
 template <> struct Frag<16> { typedef half8_t type; };
 template <int V> __host__ __device__ constexpr int frag_elems() { return V == 16 ? 8 : 4; }
 
-template <int M, int V>
-__device__ __forceinline__ void mfma_block_to_lds(float* buf, int c, int iblk, int lane,
-                                                  typename Frag<V>::type cfrag, typename Frag<V>::type xfrag)
+// Stores a block's 16 accumulators per lane into the Psumbook buffer `buf` (codebook c, centroids 32*iblk..+31).
+template <int M>
+__device__ __forceinline__ void block_to_lds(float* buf, int c, int iblk, int lane, float16_t d)
 {
-    float16_t d = {0};
-    if constexpr (V == 16) {
-        d = __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_shufflevector(cfrag, cfrag, 0, 1, 2, 3),
-                                                 __builtin_shufflevector(xfrag, xfrag, 0, 1, 2, 3), d, 0, 0, 0);
-        d = __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_shufflevector(cfrag, cfrag, 4, 5, 6, 7),
-                                                 __builtin_shufflevector(xfrag, xfrag, 4, 5, 6, 7), d, 0, 0, 0);
-    } else {
-        d = __builtin_amdgcn_mfma_f32_32x32x8f16(cfrag, xfrag, d, 0, 0, 0);
-    }
     // The lane's first destination as an LDS byte address the optimiser cannot see through:
     // the 16 stores then differ only by small immediate offsets (and pair up into two-dword
     // writes) instead of each getting an address register of its own when the buffer's
@@ -153,6 +144,28 @@ __device__ __forceinline__ void mfma_block_to_lds(float* buf, int c, int iblk, i
             *reinterpret_cast<lds_float*>(static_cast<uintptr_t>(dst + (uint32_t)(8 * blk + e) * 256u)) = d[4 * blk + e];
 }
 
+// One 32x32 block of a Psumbook: 32 centroids x 32 slots, contracted over the v elements.
+template <int V>
+__device__ __forceinline__ float16_t mfma_block(typename Frag<V>::type cfrag, typename Frag<V>::type xfrag)
+{
+    float16_t d = {0};
+    if constexpr (V == 16) {
+        d = __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_shufflevector(cfrag, cfrag, 0, 1, 2, 3),
+                                                 __builtin_shufflevector(xfrag, xfrag, 0, 1, 2, 3), d, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_shufflevector(cfrag, cfrag, 4, 5, 6, 7),
+                                                 __builtin_shufflevector(xfrag, xfrag, 4, 5, 6, 7), d, 0, 0, 0);
+    } else {
+        d = __builtin_amdgcn_mfma_f32_32x32x8f16(cfrag, xfrag, d, 0, 0, 0);
+    }
+    return d;
+}
+
+template <int M, int V>
+__device__ __forceinline__ void mfma_block_to_lds(float* buf, int c, int iblk, int lane,
+                                                  typename Frag<V>::type cfrag, typename Frag<V>::type xfrag)
+{
+    block_to_lds<M>(buf, c, iblk, lane, mfma_block<V>(cfrag, xfrag));
+}
 // The fp16 Psumbook (plan field psum_dtype = 1): an entry is the pair of partial sums of one
 // centroid index and slot for the two codebooks of a superplane, rounded to nearest-even
 // fp16 and packed into one 32-bit word: codebook 2*sp in the low half, 2*sp + 1 in the
@@ -495,12 +508,17 @@ __device__ __forceinline__ float accumulate(float acc, float psum, _Float16 scal
     else return acc + psum;
 }
 
-template <int M, int V, int NW, int RPL, int BG, int D, bool GS, bool PH = false>
+template <int M, int V, int NW, int RPL, int BG, int D, bool GS, bool PH = false, int NB = 0>
 __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
 {
     constexpr int NTILES = 8 * M;                      // 32x32 MFMA blocks in one Psumbook
     constexpr int TPW = PH ? 1 : (NTILES + NW - 1) / NW;   // blocks per wavefront (fp32 Psumbook)
-    constexpr int PIECES = RPL * NW;                   // 16-row pieces (one row word of one wavefront) per workgroup
+    // NB > 0: the last NB wavefronts build every Psumbook and do nothing else; the first NG
+    // stream, gather and reduce and never touch the matrix cores.  A wavefront issues in program
+    // order, so one that builds between two gathers delays its own next lookups and loads by the
+    // length of its build; split up, the builders run a whole unit ahead of the gatherers.
+    constexpr int NG = NW - NB;                        // wavefronts that own rows
+    constexpr int PIECES = RPL * NG;                   // 16-row pieces (one row word of one wavefront) per workgroup
     typedef PsumLayout<M> L;
     typedef PsumLayoutH<M> LH;
     constexpr int NBUF = PH ? 2 : L::kBuffers;
@@ -514,6 +532,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
     static_assert(NW == 8 || NW == 14 || NW == 16, "8, 14 or 16 wavefronts");
     static_assert(!PH || NW != 14, "the fp16 Psumbook pairs up 8 or 16 wavefronts");
     static_assert((D & 1) == 0, "ring depth must be even (buffer parity is compile-time)");
+    static_assert(NB == 0 || (!PH && BG == 1 && D == 2 && NBUF == 2 && NTILES % NB == 0),
+                  "build-only wavefronts: one batch row, double-buffered fp32 Psumbook");
 
     extern __shared__ __align__(16) unsigned char smem[];
     float* planes = reinterpret_cast<float*>(smem);                     // NBUF buffers of L::kBytes
@@ -546,7 +566,10 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
     // Centroid operands of this wavefront's MFMA blocks: fixed for the whole kernel.
     frag_t cfrag[TPW];
     frag_t cpair[PH ? PPW : 1][2];                     // fp16 Psumbook: both codebooks of this wavefront's pairs
-    if constexpr (!PH) {
+    if constexpr (NB > 0) {
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) cfrag[i] = zero4;    // the builders keep their own (below)
+    } else if constexpr (!PH) {
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
             int tile = wave + i * NW;                      // c*8 + iblk
@@ -577,7 +600,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
                                                        0, x_elems * 2, kRsrcFlags);
     }
     const int x_off0 = kvalid ? ((lane & 31) * V + FE * khalf) * 2 : kOutOfRange;
-    auto load_x = [&](int u, int bb) -> frag_t {
+    auto load_x_raw = [&](int u, int bb) -> frag_t {
         if constexpr (V == 16) {
             const u32x4_t t = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc[bb], x_off0 + u * (32 * V * 2), 0, 0);
             return __builtin_bit_cast(frag_t, t);
@@ -586,12 +609,17 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
             return __builtin_bit_cast(frag_t, t);
         }
     };
+    // what the gathering wavefronts load: nothing when others build for them
+    auto load_x = [&](int u, int bb) -> frag_t {
+        if constexpr (NB > 0) return zero4;
+        else return load_x_raw(u, bb);
+    };
     // Codes of unit u for this lane: RPL words of 8*M bytes (8 rows x M codebooks at one slot).
     // Word q (q < RPL) of this wavefront is piece blk*PIECES + q*NW + wave of the matrix: rows
     // 16*piece .. 16*piece+15, i.e. row-lanes 2*(piece%8), +1 of granule piece/8.  With 8 or 16
     // wavefronts piece%8 = wave%8 for every q; with 14 it differs from word to word.
     constexpr int kUnitBytes = 128 * 32 * M;
-    auto piece_of = [&](int q) -> int { return blk * PIECES + q * NW + wave; };
+    auto piece_of = [&](int q) -> int { return blk * PIECES + q * NG + wave; };
     auto granule_of = [&](int q) -> int { return piece_of(q) >> 3; };
     int entry[RPL];                                    // (row-lane, slot) index inside the unit
 #pragma unroll
@@ -649,6 +677,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
     bool first_build = true;
 #endif
     auto build = [&](float* buf, int par, frag_t xf) {
+        if constexpr (NB > 0) return;                  // not this wavefront's job
 #if CODEGEMM_ABLATE & 4
         // ablation build: only the first Psumbook is built; the activations are still consumed
         if (!first_build) { asm volatile("" :: "v"(xf)); return; }
@@ -671,6 +700,55 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
             }
         }
     };
+
+    if constexpr (NB > 0) {
+        if (wave >= NG) {
+            // A builder: the blocks (wave - NG) + i * NB of every Psumbook, one unit ahead of the
+            // gatherers, through the same barriers (one after the first table, one per unit).
+            constexpr int TB = NTILES / NB;
+            frag_t cb[TB];
+#pragma unroll
+            for (int i = 0; i < TB; ++i) {
+                const int tile = (wave - NG) + i * NB;
+                cb[i] = *reinterpret_cast<const frag_t*>(mm.codebooks + (size_t)(tile * 32 + (lane & 31)) * V + (kvalid ? FE * khalf : 0));
+                if (!kvalid) cb[i] = zero4;
+            }
+            // software pipeline: the product of the next block is issued before the stores of the
+            // current one, so the matrix core works while the LDS takes the stores
+            auto build_all = [&](float* buf, frag_t xf) {
+                float16_t cur = mfma_block<V>(cb[0], xf);
+#pragma unroll
+                for (int i = 0; i < TB; ++i) {
+                    float16_t nxt = cur;
+                    if (i + 1 < TB) nxt = mfma_block<V>(cb[i + 1], xf);
+                    __builtin_amdgcn_sched_barrier(0);
+                    const int tile = (wave - NG) + i * NB;
+                    block_to_lds<M>(buf, tile / 8, tile % 8, lane, cur);
+                    __builtin_amdgcn_sched_barrier(0);
+                    cur = nxt;
+                }
+            };
+            frag_t x0 = load_x_raw(0, 0), x1 = load_x_raw(1, 0);
+            build_all(planes, x0);
+            x0 = load_x_raw(2, 0);
+            __syncthreads();
+#if CODEGEMM_ABLATE & 4
+            constexpr bool kRebuild = false;   // ablation build: only the first Psumbook is built
+#else
+            constexpr bool kRebuild = true;
+#endif
+            for (int u0 = 0; u0 < nq; u0 += 2) {
+                if (kRebuild && u0 + 1 < nq) build_all(planes + L::kBytes / 4, x1);     // while unit u0 is gathered from buffer 0
+                x1 = load_x_raw(u0 + 3, 0);
+                __syncthreads();
+                if (kRebuild && u0 + 2 < nq) build_all(planes, x0);                     // while unit u0 + 1 is gathered from buffer 1
+                x0 = load_x_raw(u0 + 4, 0);
+                __syncthreads();
+            }
+            finish_block<NW * kWave, BG, PIECES * 16>(p, mm, planes, flag, tid, blk, ks, b0);
+            return;
+        }
+    }
 
     // Prologue: activations of the first D units, then the codes of the first unit only; the
     // rest of the code ring is requested after the first Psumbook has been written.  A
@@ -833,7 +911,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
 #pragma unroll
         for (int q0 = 0; q0 < RPL; q0 += NV / 8) {
             const int q = q0 + idx / 8;
-            const int local = (q * NW + wave) * 16 + khalf * kRowsPerLane + idx % 8;   // piece, half-wavefront, row
+            const int local = (q * NG + wave) * 16 + khalf * kRowsPerLane + idx % 8;   // piece, half-wavefront, row
 #pragma unroll
             for (int bb = 0; bb < BG; ++bb) {
                 float v[NV];
@@ -849,10 +927,10 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
 
 int set_max_lds(const void* fn, size_t bytes);
 
-template <int M, int V, int NW, int RPL, int BG, int D, bool GS, bool PH = false>
+template <int M, int V, int NW, int RPL, int BG, int D, bool GS, bool PH = false, int NB = 0>
 int launch_gemm_one(const Geometry& g, const GemmParams& p, hipStream_t stream)
 {
-    auto fn = gemm_kernel<M, V, NW, RPL, BG, D, GS, PH>;
+    auto fn = gemm_kernel<M, V, NW, RPL, BG, D, GS, PH, NB>;
     typedef PsumLayout<M> L;
     const size_t lds = (PH ? (size_t)PsumLayoutH<M>::kBytes : (size_t)L::kBuffers * L::kBytes) + 64;
     int st = set_max_lds(reinterpret_cast<const void*>(fn), lds);
@@ -871,6 +949,11 @@ int launch_gemm_one(const Geometry& g, const GemmParams& p, hipStream_t stream)
 template <int M, int V, int BG, bool GS>
 int launch_gemm_mvb(const Geometry& g, const GemmParams& p, hipStream_t stream)
 {
+    if constexpr (BG == 1 && M <= 2) {
+        // 14 gathering + 2 building wavefronts: 448-row blocks
+        if (g.NW == 16 && g.RPL == 2 && g.NB == 2) return launch_gemm_one<M, V, 16, 2, BG, 2, GS, false, 2>(g, p, stream);
+    }
+    if (g.NB != 0) return CODEGEMM_UNSUPPORTED;
     if (g.NW == 8 && g.RPL == 1) return launch_gemm_one<M, V, 8, 1, BG, 2, GS>(g, p, stream);
     if (g.NW == 16 && g.RPL == 1) return launch_gemm_one<M, V, 16, 1, BG, 2, GS>(g, p, stream);
     if constexpr (BG * M <= 4) {

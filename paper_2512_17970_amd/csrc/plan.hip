@@ -37,8 +37,15 @@ static int validate_plan(const codegemm_desc* d, const codegemm_plan* p)
     if (p->row_words == 4 && p->waves != 16 && p->batch_group != 4) return CODEGEMM_UNSUPPORTED;
     if (p->k_splits < 1) return CODEGEMM_UNSUPPORTED;
     if (p->batch_group != 1 && p->batch_group != 2 && p->batch_group != 4) return CODEGEMM_UNSUPPORTED;
-    for (int i = 0; i < 3; ++i)
+    for (int i = 0; i < 2; ++i)
         if (p->reserved[i]) return CODEGEMM_INVALID_ARG;
+    if (p->build_waves != 0 && p->build_waves != 2) return CODEGEMM_UNSUPPORTED;
+    if (p->build_waves == 2) {
+        // 14 gathering + 2 building wavefronts: one batch row, a double-buffered fp32 Psumbook (one or two codebooks)
+        if (p->waves != 16 || p->row_words != 2 || p->batch_group != 1 || p->psum_dtype != CODEGEMM_PSUM_FP32 ||
+            d->num_codebooks > 2)
+            return CODEGEMM_UNSUPPORTED;
+    }
     if (p->psum_dtype != CODEGEMM_PSUM_FP32 && p->psum_dtype != CODEGEMM_PSUM_FP16) return CODEGEMM_UNSUPPORTED;
     if (p->psum_dtype == CODEGEMM_PSUM_FP16) {
         if (p->batch_group != 1 || p->row_words > 2) return CODEGEMM_UNSUPPORTED;
@@ -147,12 +154,20 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
     // into 256 of 448.  Measured at 8192->28672: -2 % to -5 % for one and three codebooks and with
     // group scales; with two or four codebooks and one scale per row a tie or a loss (+0.1 us),
     // because the 8m MFMA blocks of a Psumbook then divide evenly over 16 wavefronts and not over 14.
+    // With one or two codebooks the 448 rows go to 14 of 16 wavefronts and the other two build
+    // every Psumbook, one unit ahead (build_waves = 2), when a workgroup has at least four units
+    // to stream: 8192->28672 v8 m1 10.0 -> 9.8 us, v4 m1 15.3 -> 14.0, v4 m1 g128 19.3 -> 17.0,
+    // m2v8g128 15.6 -> 15.2 against the 14-wavefront shape (two codebooks, one scale per row: 14.5 both).
     if (p->waves == 16 && p->row_words == 2 && ((m & 1) || d->group_size > 0)) {
         p->waves = 14;
         int wgs14 = 0;
         const int nks14 = ranges(2, &wgs14);
         if (wgs14 > wgs && wgs >= 192) {
             p->k_splits = nks14;
+            if (m <= 2 && ceil_div(nkt, nks14) >= 4) {
+                p->waves = 16;
+                p->build_waves = 2;
+            }
             return;
         }
         p->waves = 16;
@@ -185,12 +200,13 @@ int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g
     g->m = d->num_codebooks;
     g->J = g->K / g->v;
     g->NW = plan->waves;
+    g->NB = plan->build_waves;
     g->RPL = plan->row_words;
     g->BG = plan->batch_group;
     g->psum_fp16 = plan->psum_dtype == CODEGEMM_PSUM_FP16;
     g->NGR = ceil_div(g->N, kGranuleRows);
     // rows per workgroup: 16 per wavefront and row word (32 in the batched kernel)
-    g->NBLK = ceil_div(g->NGR * kGranuleRows, g->RPL * g->NW * (g->BG == 4 ? 32 : 16));
+    g->NBLK = ceil_div(g->NGR * kGranuleRows, g->RPL * (g->NW - g->NB) * (g->BG == 4 ? 32 : 16));
     g->NKT = ceil_div(g->J, kSlots);
     int nks = plan->k_splits < g->NKT ? plan->k_splits : g->NKT;
     g->KPW = ceil_div(g->NKT, nks);

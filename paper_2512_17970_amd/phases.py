@@ -40,7 +40,7 @@ def workgroups(desc: binding.Desc, plan: binding.Plan) -> int:
     """Workgroups of one batch group under `plan` (row blocks x K ranges)."""
     J = desc.in_features // desc.vec_len
     ngr, nkt = -(-desc.out_features // 128), -(-J // 32)
-    rows = plan.row_words * plan.waves * (32 if plan.batch_group == 4 else 16)     # rows of one workgroup
+    rows = plan.row_words * (plan.waves - plan.build_waves) * (32 if plan.batch_group == 4 else 16)     # rows of one workgroup
     nblk = -(-ngr * 128 // rows)
     nks = min(plan.k_splits, nkt)
     kpw = -(-nkt // nks)

@@ -112,7 +112,7 @@ def test_default_plans_are_valid_for_all_workloads():
             ngr = -(-c.N // 128)
             nkt = -(-c.J // 32)
             assert p.row_words in (1, 2, 4)
-            rows = p.row_words * p.waves * (32 if p.batch_group == 4 else 16)    # rows per workgroup
+            rows = p.row_words * (p.waves - p.build_waves) * (32 if p.batch_group == 4 else 16)    # rows per workgroup
             nblk = -(-ngr * 128 // rows) * (-(-c.B // p.batch_group) if p.batch_group == 4 else 1)
             assert 1 <= p.k_splits <= nkt and nblk * p.k_splits <= max(256, nblk)
             assert cg.codegemm_packed_codes_bytes(d) == ngr * 128 * nkt * 32 * c.m
@@ -225,9 +225,12 @@ def test_grouped_launch_host_validation():
 
 def test_448_row_blocks_in_plans():
     """Heights of 7 * 2^k rows get 14-wavefront workgroups by default where those fill more compute units."""
+    from paper_2512_17970_amd import phases
     for m, g in ((1, -1), (3, -1), (2, 128)):
         p = cg.codegemm_default_plan(cg.Desc.make(1, 8192, 28672, 8, m, g=g))
-        assert (p.waves, p.row_words, p.k_splits) == (14, 2, 4), (m, g)     # 64 blocks x 4 K ranges = 256 workgroups
+        # 64 blocks x 4 K ranges = 256 workgroups; with one or two codebooks 14 of 16 wavefronts own the rows and two build
+        assert (p.waves - p.build_waves, p.row_words, p.k_splits) == (14, 2, 4), (m, g)
+        assert p.build_waves == (2 if m <= 2 else 0)
     p = cg.codegemm_default_plan(cg.Desc.make(1, 8192, 28672, 8, 2))
     assert (p.waves, p.row_words, p.k_splits) == (16, 2, 4)                 # two codebooks, one scale per row: no gain measured
     p = cg.codegemm_default_plan(cg.Desc.make(1, 28672, 8192, 8, 2))
@@ -238,5 +241,13 @@ def test_448_row_blocks_in_plans():
     assert cg.codegemm_workspace_bytes(d, cg.Plan.make(14, 2, 2, 1, binding.PSUM_FP16)) == 0
     assert cg.codegemm_workspace_bytes(cg.Desc.make(8, 2048, 1000, 8, 2), cg.Plan.make(14, 2, 2, 4)) == 0
     assert cg.codegemm_workspace_bytes(cg.Desc.make(1, 2048, 1000, 8, 3), cg.Plan.make(14, 2, 2, 2)) == 0   # registers
-    from paper_2512_17970_amd import phases
+    # build-only wavefronts: 16 wavefronts, two row words, one batch row, fp32 Psumbook, at most two codebooks
+    assert cg.codegemm_workspace_bytes(d, cg.Plan.make(16, 2, 2, 1, 0, 2)) == 65536 + 2 * 1024 * 4
+    assert cg.codegemm_workspace_bytes(d, cg.Plan.make(16, 1, 2, 1, 0, 2)) == 0
+    assert cg.codegemm_workspace_bytes(d, cg.Plan.make(8, 2, 2, 1, 0, 2)) == 0
+    assert cg.codegemm_workspace_bytes(d, cg.Plan.make(16, 2, 2, 1, 0, 1)) == 0
+    assert cg.codegemm_workspace_bytes(d, cg.Plan.make(16, 2, 2, 1, binding.PSUM_FP16, 2)) == 0
+    assert cg.codegemm_workspace_bytes(cg.Desc.make(2, 2048, 1000, 8, 2), cg.Plan.make(16, 2, 2, 2, 0, 2)) == 0
+    assert cg.codegemm_workspace_bytes(cg.Desc.make(1, 2048, 1000, 8, 3), cg.Plan.make(16, 2, 2, 1, 0, 2)) == 0
+    assert phases.workgroups(cg.Desc.make(1, 8192, 28672, 8, 2), cg.Plan.make(16, 2, 4, 1, 0, 2)) == 256
     assert phases.workgroups(cg.Desc.make(1, 8192, 28672, 8, 2), cg.Plan.make(14, 2, 4, 1)) == 256

@@ -59,11 +59,12 @@ def test_grouped_small(K, Ns, v, m, B, g):
     run_group(K, list(Ns), v, m, B, g)
 
 
-@pytest.mark.parametrize("waves,row_words,k_splits,psum", [(8, 1, 3, 0), (16, 1, 2, 0), (16, 2, 4, 0), (8, 2, 1, 0), (8, 1, 2, 1), (14, 2, 3, 0)])
-def test_grouped_plans(waves, row_words, k_splits, psum):
+@pytest.mark.parametrize("waves,row_words,k_splits,psum,build", [(8, 1, 3, 0, 0), (16, 1, 2, 0, 0), (16, 2, 4, 0, 0), (8, 2, 1, 0, 0), (8, 1, 2, 1, 0),
+                                                                  (14, 2, 3, 0, 0), (16, 2, 3, 0, 2), (16, 2, 1, 0, 2)])
+def test_grouped_plans(waves, row_words, k_splits, psum, build):
     """Explicit plans: block heights of 128..512 rows, with and without a split of K, members whose
     heights are not multiples of the block, fp16 Psumbook."""
-    plan = cg.Plan.make(waves, row_words, k_splits, 1, psum)
+    plan = cg.Plan.make(waves, row_words, k_splits, 1, psum, build)
     run_group(2048, [700, 130, 260], 8, 2, 1, -1, plan=plan, seed=7100 + waves + row_words)
 
 

@@ -101,6 +101,19 @@ def test_448_row_blocks(N, v, m, g, B):
     run_case(case, plan=cg.Plan.make(14, 2, 2, B), dequant=False)
 
 
+@pytest.mark.parametrize("k_splits", [1, 2, 3, 1000])
+@pytest.mark.parametrize("v,m,g", [(8, 2, -1), (8, 1, -1), (4, 1, -1), (16, 2, -1), (8, 2, 128), (4, 1, 32), (8, 1, 8), (16, 1, 64), (4, 2, 4)])
+def test_build_only_wavefronts(v, m, g, k_splits):
+    """Plans with build_waves = 2: 14 wavefronts stream, gather and own 448 rows, 2 wavefronts build every Psumbook
+    one unit ahead.  Ragged N (blocks that end inside a granule), K with a ragged last unit, odd and even numbers
+    of units per workgroup (1, 2, 3, 5, 11 with the K splits above)."""
+    unit = max(g, v * 32)
+    for N, units in ((1300, 11), (448, 1), (449, 2), (31, 5)):
+        K = unit * units + (g if g > 0 else v * 7)
+        case = synth.custom_case(K, N, v, m, 1, seed=1500 + N + units, g=g)
+        run_case(case, plan=cg.Plan.make(16, 2, k_splits, 1, 0, 2), dequant=False)
+
+
 def test_batched_kernel_long_ragged_k():
     """Batch groups of 4 over a long K range with a ragged last unit and a ragged last row block."""
     for (v, m, waves, rw, splits, B) in [(8, 2, 16, 1, 1, 4), (8, 2, 8, 2, 2, 9), (4, 1, 16, 1, 1, 6), (8, 1, 8, 1, 3, 4),
