@@ -532,7 +532,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
     static_assert(NW == 8 || NW == 14 || NW == 16, "8, 14 or 16 wavefronts");
     static_assert(!PH || NW != 14, "the fp16 Psumbook pairs up 8 or 16 wavefronts");
     static_assert((D & 1) == 0, "ring depth must be even (buffer parity is compile-time)");
-    static_assert(NB == 0 || (!PH && BG == 1 && D == 2 && NBUF == 2 && NTILES % NB == 0),
+    static_assert(NB == 0 || (!PH && BG == 1 && NBUF == 2 && NTILES % NB == 0),
                   "build-only wavefronts: one batch row, double-buffered fp32 Psumbook");
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -728,22 +728,25 @@ __global__ void __launch_bounds__(NW * 64) gemm_kernel(const GemmParams p)
                     cur = nxt;
                 }
             };
-            frag_t x0 = load_x_raw(0, 0), x1 = load_x_raw(1, 0);
-            build_all(planes, x0);
-            x0 = load_x_raw(2, 0);
+            frag_t xs[2] = {load_x_raw(0, 0), load_x_raw(1, 0)};
+            build_all(planes, xs[0]);
+            xs[0] = load_x_raw(2, 0);
             __syncthreads();
 #if CODEGEMM_ABLATE & 4
             constexpr bool kRebuild = false;   // ablation build: only the first Psumbook is built
 #else
             constexpr bool kRebuild = true;
 #endif
-            for (int u0 = 0; u0 < nq; u0 += 2) {
-                if (kRebuild && u0 + 1 < nq) build_all(planes + L::kBytes / 4, x1);     // while unit u0 is gathered from buffer 0
-                x1 = load_x_raw(u0 + 3, 0);
-                __syncthreads();
-                if (kRebuild && u0 + 2 < nq) build_all(planes, x0);                     // while unit u0 + 1 is gathered from buffer 1
-                x0 = load_x_raw(u0 + 4, 0);
-                __syncthreads();
+            // the gatherers' loop, barrier for barrier: while they gather unit u from buffer u % 2,
+            // unit u + 1 is built into the other one
+            for (int u0 = 0; u0 < nq; u0 += D) {
+#pragma unroll
+                for (int d = 0; d < D; ++d) {
+                    const int u = u0 + d;
+                    if (kRebuild && u + 1 < nq) build_all(planes + ((d + 1) & 1) * (L::kBytes / 4), xs[(d + 1) & 1]);
+                    xs[(d + 1) & 1] = load_x_raw(u + 3, 0);
+                    __syncthreads();
+                }
             }
             finish_block<NW * kWave, BG, PIECES * 16>(p, mm, planes, flag, tid, blk, ks, b0);
             return;
