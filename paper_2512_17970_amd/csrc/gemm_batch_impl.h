@@ -51,7 +51,7 @@ __device__ __forceinline__ float4_t psum4_at(uint32_t word, uint32_t off)
     return *reinterpret_cast<const lds_float4*>(static_cast<uintptr_t>(addr));
 }
 
-template <int M, int V, int NW, int RPL, int D, bool GS>
+template <int M, int V, int NW, int RPL, int D, bool GS, int NB = 0>
 __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
 {
     constexpr int BG = 4;                              // batch rows per pass
@@ -61,10 +61,14 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
     constexpr int TPW = (NBLOCKS + NW - 1) / NW;       // blocks per wavefront
     constexpr int XN = (M == 1) ? TPW : 1;             // distinct activation operands per wavefront and tile
     constexpr int SP = (M + 1) / 2;                    // superplanes
-    constexpr int GPW = RPL * NW / 4;                  // 128-row granules per workgroup
+    // NB > 0: the last NB wavefronts build every Psumbook and nothing else, one tile ahead; the
+    // first NG stream, gather and own the rows (see the batch-1 kernel).
+    constexpr int NG = NW - NB;                        // wavefronts that own rows
+    constexpr int PIECES = RPL * NG;                   // 32-row pieces (one row word of one wavefront) per workgroup
     typedef PsumLayout<M> L;
     constexpr int NBUF = L::kBuffers;
     static_assert(NW == 8 || NW == 16, "8 or 16 wavefronts");
+    static_assert(NB == 0 || (NBUF == 2 && NBLOCKS % NB == 0 && 8 % NB == 0), "build-only wavefronts: a double-buffered Psumbook");
     static_assert((D & 1) == 0, "ring depth must be even (buffer parity is compile-time)");
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -76,7 +80,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be: keeps buffer descriptors in scalar registers
     const int ks = blockIdx.x;
     const Member mm = member_of(p, blockIdx.y);        // the layer this workgroup works for
-    const int blk = blockIdx.y - mm.blk0;              // its row block of GPW granules
+    const int blk = blockIdx.y - mm.blk0;              // its row block of PIECES x 32 rows
     const int b0 = blockIdx.z * BG;
     const int kt0 = ks * p.KPW;
     const int nq = min(p.KPW, p.NKT - kt0);            // units of this workgroup (>= 1 by construction)
@@ -114,7 +118,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
         int t = wave + i * NW;
         if (t >= NBLOCKS) t = NBLOCKS - 1;
         const int cb = (M == 1) ? 0 : t / 8;
-        cfrag[i] = *reinterpret_cast<const frag_t*>(mm.codebooks + (size_t)((cb * 8 + t % 8) * 32 + (lane & 31)) * V + (kvalid ? FE * khalf : 0));
+        if constexpr (NB > 0) cfrag[i] = zero4;        // the builders keep their own (below)
+        else cfrag[i] = *reinterpret_cast<const frag_t*>(mm.codebooks + (size_t)((cb * 8 + t % 8) * 32 + (lane & 31)) * V + (kvalid ? FE * khalf : 0));
     }
     // Activation operand (Step 1): column n = lane % 32 of a block is (slot n / 4, batch row
     // n % 4); the lane supplies elements 4 * (lane / 32)..+3 of that sub-vector.  One
@@ -132,6 +137,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
         if (!(kvalid && x_row < p.B)) x_j0[i] = J;                    // never valid
     }
     auto load_x = [&](int t, int i) -> frag_t {
+        if constexpr (NB > 0) return zero4;            // a gathering wavefront loads no activations
         const bool ok = x_j0[i] + t * TS < J;
         const int off = ok ? x_off0[i] + t * (TS * V * 2) : kOutOfRange;
         if constexpr (V == 16) {
@@ -141,24 +147,30 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
         }
     };
     // Codes of tile t for this lane: per row word q and superplane, the 8 bytes (8 rows) of
-    // its codebook at its slot.  Word q of this wavefront belongs to granule
-    // blk * GPW + q * (NW / 4) + wave / 4, row octet 4 * (wave % 4) + oct.
+    // its codebook at its slot.  Word q of this wavefront is piece blk * PIECES + q * NG + wave of
+    // the matrix: rows 32 * piece .. +31, i.e. row octets 4 * (piece % 4) + oct of granule piece / 4
+    // (piece % 4 = wave % 4 for every q unless 14 wavefronts own the rows).
     constexpr int kUnitBytes = 128 * 32 * M;
-    const int g16 = (wave % 4) * 4 + oct;
+    auto piece_of = [&](int q) -> int { return blk * PIECES + q * NG + wave; };
+    int g16[RPL];
+#pragma unroll
+    for (int q = 0; q < RPL; ++q) g16[q] = (piece_of(q) & 3) * 4 + oct;
     __amdgpu_buffer_rsrc_t c_rsrc[RPL];
 #pragma unroll
     for (int q = 0; q < RPL; ++q) {
-        const int gr = blk * GPW + q * (NW / 4) + wave / 4;
+        const int gr = piece_of(q) >> 2;
         const uint8_t* base = mm.packed + ((size_t)min(gr, mm.NGR - 1) * p.NKT + kt0) * kUnitBytes;
         c_rsrc[q] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, gr < mm.NGR ? nq * kUnitBytes : 0, kRsrcFlags);
     }
-    int c_off[SP];
+    int c_off[RPL][SP];
 #pragma unroll
-    for (int sp = 0; sp < SP; ++sp) {
-        const bool single = (2 * sp + 1 == M);         // last part of an odd M: 8 bytes per entry, one codebook
-        if (single) c_off[sp] = (par_cb == 0) ? sp * 8192 + (g16 * kSlots + slot) * 8 : kOutOfRange;
-        else c_off[sp] = sp * 8192 + (g16 * kSlots + slot) * 16 + 8 * par_cb;
-    }
+    for (int q = 0; q < RPL; ++q)
+#pragma unroll
+        for (int sp = 0; sp < SP; ++sp) {
+            const bool single = (2 * sp + 1 == M);         // last part of an odd M: 8 bytes per entry, one codebook
+            if (single) c_off[q][sp] = (par_cb == 0) ? sp * 8192 + (g16[q] * kSlots + slot) * 8 : kOutOfRange;
+            else c_off[q][sp] = sp * 8192 + (g16[q] * kSlots + slot) * 16 + 8 * par_cb;
+        }
     auto load_codes = [&](uint32_t (&dst)[RPL][SP][2], int t) {
         const int toff = (t / TPU) * kUnitBytes + (t % TPU) * TS * 16;
 #pragma unroll
@@ -166,7 +178,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
 #pragma unroll
             for (int sp = 0; sp < SP; ++sp) {
                 const bool single = (2 * sp + 1 == M);
-                const int o = c_off[sp] + (single ? (t / TPU) * kUnitBytes + (t % TPU) * TS * 8 : toff);
+                const int o = c_off[q][sp] + (single ? (t / TPU) * kUnitBytes + (t % TPU) * TS * 8 : toff);
                 const u32x2_t r = __builtin_amdgcn_raw_buffer_load_b64(c_rsrc[q], o, 0, 2);
                 dst[q][sp][0] = r.x;
                 dst[q][sp][1] = r.y;
@@ -181,19 +193,20 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
     if constexpr (GS) {
 #pragma unroll
         for (int q = 0; q < RPL; ++q) {
-            const int gr = blk * GPW + q * (NW / 4) + wave / 4;
+            const int gr = piece_of(q) >> 2;
             const uint8_t* base = mm.gscales + ((size_t)min(gr, mm.NGR - 1) * p.NKT + kt0) * p.GPU * 256;
             s_rsrc[q] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, gr < mm.NGR ? nq * p.GPU * 256 : 0, kRsrcFlags);
         }
     }
     auto load_scales = [&](half8_t (&dst)[RPL], int t) {
         const int group = ((t % TPU) * TS + slot) >> p.gshift;       // of the tile's unit
-        const int o = ((t / TPU) * p.GPU + group) * 256 + g16 * 16;
+        const int o = ((t / TPU) * p.GPU + group) * 256;
 #pragma unroll
         for (int q = 0; q < RPL; ++q)
-            dst[q] = __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(s_rsrc[GS ? q : 0], o, 0, 0));
+            dst[q] = __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(s_rsrc[GS ? q : 0], o + g16[q] * 16, 0, 0));
     };
     auto build = [&](float* buf, const frag_t (&xf)[XN]) {
+        if constexpr (NB > 0) return;                  // not this wavefront's job
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
             const int t = wave + i * NW;
@@ -202,6 +215,72 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
                 mfma_block_to_lds<(M == 1) ? 2 : M, V>(buf, t / 8, t % 8, lane, kvalid ? cfrag[i] : zero4, xf[(M == 1) ? i : 0]);
         }
     };
+
+    if constexpr (NB > 0) {
+        if (wave >= NG) {
+            // A builder: blocks (wave - NG) + i * NB of every tile's Psumbook, one tile ahead of the
+            // gatherers, through the same barriers (one after the first table, one per tile).
+            constexpr int TB = NBLOCKS / NB;
+            constexpr int XB = (M == 1) ? 2 : 1;       // one codebook: the two slot halves have their own operands
+            frag_t cb[TB];
+#pragma unroll
+            for (int i = 0; i < TB; ++i) {
+                const int t = (wave - NG) + i * NB;
+                const int c = (M == 1) ? 0 : t / 8;
+                cb[i] = *reinterpret_cast<const frag_t*>(mm.codebooks + (size_t)((c * 8 + t % 8) * 32 + (lane & 31)) * V + (kvalid ? FE * khalf : 0));
+                if (!kvalid) cb[i] = zero4;
+            }
+            int xb_j0[XB], xb_off0[XB];
+#pragma unroll
+            for (int h = 0; h < XB; ++h) {
+                xb_j0[h] = kt0 * kSlots + h * 8 + ((lane & 31) >> 2);
+                xb_off0[h] = (x_row * p.K + xb_j0[h] * V + FE * khalf) * 2;
+                if (!(kvalid && x_row < p.B)) xb_j0[h] = J;                   // never valid
+            }
+            auto load_xb = [&](frag_t (&dst)[XB], int t) {
+#pragma unroll
+                for (int h = 0; h < XB; ++h) {
+                    const bool ok = xb_j0[h] + t * TS < J;
+                    const int off = ok ? xb_off0[h] + t * (TS * V * 2) : kOutOfRange;
+                    if constexpr (V == 16) dst[h] = __builtin_bit_cast(frag_t, __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, off, 0, 0));
+                    else dst[h] = __builtin_bit_cast(frag_t, __builtin_amdgcn_raw_buffer_load_b64(x_rsrc, off, 0, 0));
+                }
+            };
+            // software pipeline: the product of the next block is issued before the stores of the current one
+            auto build_all = [&](float* buf, const frag_t (&xf)[XB]) {
+                float16_t cur = mfma_block<V>(cb[0], xf[0]);
+#pragma unroll
+                for (int i = 0; i < TB; ++i) {
+                    float16_t nxt = cur;
+                    // (block t belongs to slot half t / 8 = i * NB / 8: NB divides 8, so the wavefront's own
+                    // offset never carries into it and the operand index is a compile-time constant)
+                    if (i + 1 < TB) nxt = mfma_block<V>(cb[i + 1], xf[(M == 1) ? ((i + 1) * NB) / 8 : 0]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    const int t = (wave - NG) + i * NB;
+                    block_to_lds<(M == 1) ? 2 : M>(buf, t / 8, t % 8, lane, cur);
+                    __builtin_amdgcn_sched_barrier(0);
+                    cur = nxt;
+                }
+            };
+            frag_t xs[2][XB];
+            load_xb(xs[0], 0);
+            load_xb(xs[1], 1);
+            build_all(planes, xs[0]);
+            load_xb(xs[0], 2);
+            __syncthreads();
+            for (int t0 = 0; t0 < ntiles; t0 += D) {
+#pragma unroll
+                for (int d = 0; d < D; ++d) {
+                    const int t = t0 + d;
+                    if (t + 1 < ntiles) build_all(planes + ((d + 1) & 1) * (L::kBytes / 4), xs[(d + 1) & 1]);
+                    load_xb(xs[(d + 1) & 1], t + 3);
+                    __syncthreads();
+                }
+            }
+            finish_block<NW * kWave, BG, PIECES * 32>(p, mm, planes, flag, tid, blk, ks, b0);
+            return;
+        }
+    }
 
     // Prologue: activations of the first D tiles and codes of the first; the rest of the code
     // ring is requested after the first Psumbook has been written (as in the batch-1 kernel).
@@ -294,7 +373,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
 
     // Row totals = sums over the 16 lanes of a DPP row; parked in LDS (the Psumbook is no
     // longer needed) as [batch row][row of the block].
-    constexpr int ROWS = GPW * kGranuleRows;
+    constexpr int ROWS = PIECES * 32;
     float* stage = planes;
     {
         const int l = lane & 15;
@@ -306,7 +385,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
 #pragma unroll
             for (int i = 0; i < 32; ++i) v[i] = acc[q][i >> 2][i & 3];
             row16_transpose_sum(v, lane);
-            const int local = (q * (NW / 4) + wave / 4) * kGranuleRows + g16 * kRowsPerLane + r;
+            const int local = (q * NG + wave) * 32 + oct * kRowsPerLane + r;      // piece, row octet, row
             stage[bb * ROWS + local] = v[0];
             stage[(bb + 1) * ROWS + local] = v[1];
         }
@@ -314,10 +393,10 @@ __global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
     finish_block<NW * kWave, BG, ROWS>(p, mm, stage, flag, tid, blk, ks, b0);
 }
 
-template <int M, int V, int NW, int RPL, int D, bool GS>
+template <int M, int V, int NW, int RPL, int D, bool GS, int NB = 0>
 int launch_gemm_batch_one(const Geometry& g, const GemmParams& p, hipStream_t stream)
 {
-    auto fn = gemm_batch_kernel<M, V, NW, RPL, D, GS>;
+    auto fn = gemm_batch_kernel<M, V, NW, RPL, D, GS, NB>;
     typedef PsumLayout<M> L;
     const size_t lds = (size_t)L::kBuffers * L::kBytes + 64;
     int st = set_max_lds(reinterpret_cast<const void*>(fn), lds);
@@ -330,6 +409,12 @@ int launch_gemm_batch_one(const Geometry& g, const GemmParams& p, hipStream_t st
 template <int M, int V, bool GS>
 int launch_gemm_batch_v(const Geometry& g, const GemmParams& p, hipStream_t stream)
 {
+    if constexpr (M <= 2) {
+        // 14 gathering + 2 building wavefronts: blocks of 448 or 896 rows
+        if (g.NW == 16 && g.RPL == 1 && g.NB == 2) return launch_gemm_batch_one<M, V, 16, 1, 2, GS, 2>(g, p, stream);
+        if (g.NW == 16 && g.RPL == 2 && g.NB == 2) return launch_gemm_batch_one<M, V, 16, 2, 2, GS, 2>(g, p, stream);
+    }
+    if (g.NB != 0) return CODEGEMM_UNSUPPORTED;
     if (g.NW == 16 && g.RPL == 1) return launch_gemm_batch_one<M, V, 16, 1, 2, GS>(g, p, stream);
     if (g.NW == 8 && g.RPL == 1) return launch_gemm_batch_one<M, V, 8, 1, 2, GS>(g, p, stream);
     if (g.NW == 8 && g.RPL == 2) return launch_gemm_batch_one<M, V, 8, 2, 2, GS>(g, p, stream);

@@ -41,10 +41,10 @@ static int validate_plan(const codegemm_desc* d, const codegemm_plan* p)
         if (p->reserved[i]) return CODEGEMM_INVALID_ARG;
     if (p->build_waves != 0 && p->build_waves != 2) return CODEGEMM_UNSUPPORTED;
     if (p->build_waves == 2) {
-        // 14 gathering + 2 building wavefronts: one batch row, a double-buffered fp32 Psumbook (one or two codebooks)
-        if (p->waves != 16 || p->row_words != 2 || p->batch_group != 1 || p->psum_dtype != CODEGEMM_PSUM_FP32 ||
-            d->num_codebooks > 2)
-            return CODEGEMM_UNSUPPORTED;
+        // 14 gathering + 2 building wavefronts: a double-buffered fp32 Psumbook (one or two codebooks); one batch
+        // row per pass with two row words, or the batched kernel with one or two
+        if (p->waves != 16 || p->psum_dtype != CODEGEMM_PSUM_FP32 || d->num_codebooks > 2) return CODEGEMM_UNSUPPORTED;
+        if (p->batch_group == 1 ? p->row_words != 2 : (p->batch_group != 4 || p->row_words > 2)) return CODEGEMM_UNSUPPORTED;
     }
     if (p->psum_dtype != CODEGEMM_PSUM_FP32 && p->psum_dtype != CODEGEMM_PSUM_FP16) return CODEGEMM_UNSUPPORTED;
     if (p->psum_dtype == CODEGEMM_PSUM_FP16) {
@@ -88,7 +88,7 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
         // groups together give close to, but not more than, 256 workgroups.
         const int groups = ceil_div(batch, 4);
         auto fill = [&](int waves, int row_words, int* k_splits) {      // workgroups of a block shape
-            const int nblk = ceil_div(ngr, waves * row_words / 4) * groups;
+            const int nblk = ceil_div(ngr * kGranuleRows, waves * row_words * 32) * groups;
             int nks = 256 / nblk;
             if (nks > nkt) nks = nkt;
             if (nks < 1) nks = 1;
@@ -129,6 +129,22 @@ static void choose_plan(const codegemm_desc* d, codegemm_plan* p)
             if (w8 > wgs || (w8 >= 192 && ks8 < ks)) { p->waves = 8; p->row_words = 1; wgs = w8; ks = ks8; }
         }
         p->k_splits = ks;
+        // Heights that 448 (896) rows divide, one or two codebooks: 14 of the 16 wavefronts own the rows
+        // and 2 build every tile's Psumbook one tile ahead; the blocks then also fill 256 compute units
+        // where 512 (1024) rows give 224 (4096->14336 v8 m2, batch 4 / 8 / 16 / 32: -5 / -9 / -12 / -11 %;
+        // 8192->28672 m2v8g128 batch 4 / 8: -9 / -10 %).  With a ragged last block it loses (8192 rows: +10 %).
+        if (p->waves == 16 && m <= 2) {
+            const int rows = 14 * p->row_words * 32;
+            const int nblk14 = ceil_div(d->out_features, rows);
+            if ((long long)nblk14 * rows * 50 <= (long long)ngr * kGranuleRows * 51) {        // at most 2 % of padding
+                int ks14 = 1;
+                const int wgs14 = fill(14, p->row_words, &ks14);
+                if (wgs14 >= wgs && wgs14 >= 192) {
+                    p->k_splits = ks14;
+                    p->build_waves = 2;
+                }
+            }
+        }
         return;
     }
     // 512-row blocks for large matrices with up to three codebooks, 256-row blocks (more, shorter

@@ -250,4 +250,17 @@ def test_448_row_blocks_in_plans():
     assert cg.codegemm_workspace_bytes(cg.Desc.make(2, 2048, 1000, 8, 2), cg.Plan.make(16, 2, 2, 2, 0, 2)) == 0
     assert cg.codegemm_workspace_bytes(cg.Desc.make(1, 2048, 1000, 8, 3), cg.Plan.make(16, 2, 2, 1, 0, 2)) == 0
     assert phases.workgroups(cg.Desc.make(1, 8192, 28672, 8, 2), cg.Plan.make(16, 2, 4, 1, 0, 2)) == 256
+    # the batched kernel takes them with one or two row words
+    d8 = cg.Desc.make(8, 2048, 1000, 8, 2)
+    assert cg.codegemm_workspace_bytes(d8, cg.Plan.make(16, 1, 2, 4, 0, 2)) > 0
+    assert cg.codegemm_workspace_bytes(d8, cg.Plan.make(16, 2, 2, 4, 0, 2)) > 0
+    assert cg.codegemm_workspace_bytes(d8, cg.Plan.make(16, 4, 2, 4, 0, 2)) == 0
+    assert cg.codegemm_workspace_bytes(d8, cg.Plan.make(8, 1, 2, 4, 0, 2)) == 0
+    assert cg.codegemm_workspace_bytes(cg.Desc.make(8, 2048, 1000, 8, 3), cg.Plan.make(16, 1, 2, 4, 0, 2)) == 0
+    # defaults: heights of 7 * 2^k rows at batch 4..32 get them, heights that 448 does not divide do not
+    for B, want in ((4, (16, 1, 8, 2)), (8, (16, 2, 8, 2)), (16, (16, 2, 4, 2)), (32, (16, 2, 2, 2))):
+        p = cg.codegemm_default_plan(cg.Desc.make(B, 4096, 14336, 8, 2))
+        assert (p.waves, p.row_words, p.k_splits, p.build_waves) == want, (B, p)
+    assert cg.codegemm_default_plan(cg.Desc.make(32, 14336, 4096, 8, 2)).build_waves == 0
+    assert cg.codegemm_default_plan(cg.Desc.make(8, 8192, 28672, 8, 3)).build_waves == 0
     assert phases.workgroups(cg.Desc.make(1, 8192, 28672, 8, 2), cg.Plan.make(14, 2, 4, 1)) == 256

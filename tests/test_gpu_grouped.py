@@ -74,6 +74,8 @@ def test_grouped_plans(waves, row_words, k_splits, psum, build):
     (1024, (1100, 1030), 8, 2, 8, -1, (16, 2, 2, 4)),      # 1024-row blocks
     (2048, (300, 520, 8), 4, 1, 32, 128, None),            # group scales, a full launch of batch rows
     (1024, (384, 384), 16, 3, 5, -1, None),
+    (2048, (900, 450, 130), 8, 2, 6, -1, (16, 1, 2, 4, 0, 2)),     # 14 gathering + 2 building wavefronts
+    (1024, (1000, 896), 4, 1, 8, 32, (16, 2, 1, 4, 0, 2)),
 ])
 def test_grouped_batched_kernel(K, Ns, v, m, B, g, plan):
     """Groups through the batched kernel (4 batch rows per pass)."""

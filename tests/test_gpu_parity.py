@@ -114,6 +114,18 @@ def test_build_only_wavefronts(v, m, g, k_splits):
         run_case(case, plan=cg.Plan.make(16, 2, k_splits, 1, 0, 2), dequant=False)
 
 
+@pytest.mark.parametrize("row_words,k_splits", [(1, 1), (1, 3), (2, 2), (2, 1000)])
+@pytest.mark.parametrize("v,m,g,B", [(8, 2, -1, 4), (8, 1, -1, 8), (4, 1, -1, 5), (16, 2, -1, 3), (8, 2, 128, 32), (4, 1, 32, 6), (8, 1, 8, 4), (4, 2, 4, 7)])
+def test_build_only_wavefronts_batched(v, m, g, B, row_words, k_splits):
+    """The batched kernel with build_waves = 2: 14 wavefronts own 448 (896) rows, 2 build every tile's Psumbook one
+    tile ahead.  Ragged batch groups, ragged N and K, one to many tiles per workgroup."""
+    unit = max(g, v * 32)
+    for N, units in ((1900, 7), (896, 1), (450, 2)):
+        K = unit * units + (g if g > 0 else v * 9)
+        case = synth.custom_case(K, N, v, m, B, seed=1600 + N + units + B, g=g)
+        run_case(case, plan=cg.Plan.make(16, row_words, k_splits, 4, 0, 2), dequant=False)
+
+
 def test_batched_kernel_long_ragged_k():
     """Batch groups of 4 over a long K range with a ragged last unit and a ragged last row block."""
     for (v, m, waves, rw, splits, B) in [(8, 2, 16, 1, 1, 4), (8, 2, 8, 2, 2, 9), (4, 1, 16, 1, 1, 6), (8, 1, 8, 1, 3, 4),
