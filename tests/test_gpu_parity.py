@@ -433,6 +433,30 @@ def test_random_formats_shapes_and_plans():
         done += 1
 
 
+def test_random_shapes_with_build_only_wavefronts():
+    """Seeded random draws over the plans with build_waves = 2 (one or two codebooks, batch group 1 or 4):
+    ragged N against the 448- and 896-row blocks, ragged K, K ranges beyond the number of units."""
+    rng = np.random.default_rng(20251218)
+    done = 0
+    while done < 30:
+        v = int(rng.choice([4, 8, 16]))
+        m = int(rng.integers(1, 3))
+        B = int(rng.choice([1, 1, 3, 4, 7, 12, 32]))
+        g = int(rng.choice([-1, -1, v, 4 * v, 128]))
+        if g != -1 and g < v:
+            g = v
+        unit = max(g, v) if g != -1 else v
+        K = unit * int(rng.integers(1, max(2, 5000 // unit)))
+        N = int(rng.integers(1, 2000))
+        bg = 1 if B == 1 else 4
+        plan = cg.Plan.make(16, 2 if bg == 1 else int(rng.choice([1, 2])), int(rng.choice([1, 2, 3, 7, 64])), bg, 0, 2)
+        desc = cg.Desc.make(B, K, N, v, m, g=g)
+        if cg.codegemm_workspace_bytes(desc, plan) == 0:
+            continue                                  # plan not offered for this format
+        run_case(synth.custom_case(K, N, v, m, B, seed=8000 + done, g=g), plan=plan, dequant=False)
+        done += 1
+
+
 def test_one_workspace_serves_calls_of_different_shapes_and_plans():
     """A workspace that went through codegemm_workspace_init once is shared by calls with different
     shapes, K-range counts and kernels, interleaved and repeated: every call leaves its ticket
