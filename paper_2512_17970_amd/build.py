@@ -14,8 +14,11 @@ ABLATE_MASKS = (6, 8, 14)       # ablation builds made by default: no gather + n
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # Packed-FP32 instruction selection is switched off for every device compile.
+# Kernel-argument preloading: the leading scalar arguments of a kernel (up to 14 dwords) arrive in
+# scalar registers with the wavefront instead of being loaded from the argument segment first.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-kernarg-preload-count=14",
          "-Wall", "-Wno-unused-command-line-argument"]
 
 

@@ -52,8 +52,9 @@ __device__ __forceinline__ float4_t psum4_at(uint32_t word, uint32_t off)
 }
 
 template <int M, int V, int NW, int RPL, int D, bool GS, int NB = 0>
-__global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(const GemmParams p)
+__global__ void __launch_bounds__(NW * 64) gemm_batch_kernel(CG_HEAD_PARAMS, const GemmParams pk)
 {
+    const GemmParams p = with_head(pk, hx, hpacked, hcodebooks, hgscales, hK, hNKT, hKPW, hB, hNGR, hmisc);
     constexpr int BG = 4;                              // batch rows per pass
     constexpr int TS = (M == 1) ? 16 : 8;              // sub-vectors per tile
     constexpr int TPU = kSlots / TS;                   // tiles per 32-slot unit
@@ -402,7 +403,7 @@ int launch_gemm_batch_one(const Geometry& g, const GemmParams& p, hipStream_t st
     int st = set_max_lds(reinterpret_cast<const void*>(fn), lds);
     if (st != CODEGEMM_OK) return st;
     const dim3 grid((unsigned)g.NKS, (unsigned)g.NBLK, (unsigned)g.NG);
-    hipLaunchKernelGGL(fn, grid, dim3(NW * kWave), lds, stream, p);
+    hipLaunchKernelGGL(fn, grid, dim3(NW * kWave), lds, stream, CG_HEAD_ARGS(p), p);
     return hipGetLastError() == hipSuccess ? CODEGEMM_OK : CODEGEMM_LAUNCH_FAILED;
 }
 
