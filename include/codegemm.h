@@ -133,10 +133,13 @@ size_t codegemm_packed_codes_bytes(const codegemm_desc *desc, const codegemm_pla
  * Every codegemm_gemm call leaves the workspace ready for the next call on the
  * same stream, so this is a one-time cost; the next call may have another
  * shape, format or plan (the workspace starts with a 64 KB area of ticket
- * counters that every call finds and leaves all zero, followed by fp32 partial
- * sums that need no initial value), so one workspace of the largest
- * codegemm_workspace_bytes() serves all layers of a model.  Two calls that use
- * the same workspace concurrently (different streams) race.
+ * counters and a 2 MB area of 64-bit words through which calls with two or four
+ * K ranges combine their sums pairwise, both of which every call finds and
+ * leaves all zero, followed by fp32 partial sums that need no initial value),
+ * so one workspace of the largest codegemm_workspace_bytes() serves all layers
+ * of a model.  A call that is aborted (device reset, killed process) can leave
+ * the two areas non-zero: initialise again.  Two calls that use the same
+ * workspace concurrently (different streams) race.
  */
 int codegemm_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
@@ -263,8 +266,8 @@ int codegemm_gemm_grouped(const codegemm_desc *desc, const codegemm_plan *plan, 
  * codegemm_static_workspace_limit() bytes (8 MiB) that lives inside the loaded
  * library, one per GPU, until the process ends.  The call allocates nothing.
  * Returns CODEGEMM_WORKSPACE_TOO_SMALL when codegemm_workspace_bytes(desc, plan)
- * exceeds that limit (about batch * k_splits * N > 2 million).  The first call on
- * a device looks the array up and clears its ticket counters on `stream`; make
+ * exceeds that limit (about batch * k_splits * N > 1.5 million).  The first call on
+ * a device looks the array up and clears its counter and pair-word areas on `stream`; make
  * that call outside graph capture.  All calls on one GPU share the array: two
  * that overlap in time (different streams, or graphs replayed concurrently)
  * race; calls on one stream, of any shapes and plans, do not.

@@ -27,7 +27,10 @@ extern "C" {
  *    4 streaming loop done           5 partial sums issued
  *    6 partial sums acknowledged     7 ticket drawn
  *    8..15 unit (or tile) 0..7 done, slot 15 also for every later one
- *    16 row totals staged in LDS     17 staging barrier passed    18..23 unused
+ *    16 row totals staged in LDS     17 staging barrier passed
+ *    18 first pair add issued        19 first pair add returned   (calls that combine their K ranges
+ *    20 last pair add returned           pairwise through 64-bit words instead of ticket and partial sums)
+ *    21..23 unused
  * Process-wide state; not thread-safe.
  */
 void codegemm_set_trace(uint64_t *stamps);

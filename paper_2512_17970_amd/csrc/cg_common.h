@@ -23,6 +23,9 @@ constexpr int kGranuleRows = 128;   // rows per packed unit: 16 half-wavefronts 
 // more than 256 row blocks x batch groups AND several K ranges get a smaller stride.
 constexpr int kCounterStride = 64;
 constexpr int kCounterAreaWords = 16384;   // 64 KB
+// Behind the counters: 64-bit words of the pairwise reduction between K ranges (2, 4 or 8 of them), which every call
+// finds and leaves all zero like the counters.  Calls whose words do not fit use the ticket and the fp32 partials.
+constexpr size_t kPairAreaBytes = 2u << 20;
 constexpr int kMaxLds = 160 * 1024; // LDS per workgroup on gfx950
 constexpr int kBatchPerLaunch = 32;         // batch rows one launch of a gather kernel takes; more rows = more launches
 constexpr int kMaxBatch = 65535;            // grid limit of the comparator (one grid row per batch row)
@@ -77,7 +80,8 @@ __host__ __device__ inline size_t packed_offset(int c, int n, int j, int m, int 
 }
 
 int make_geometry(const codegemm_desc* d, const codegemm_plan* plan, Geometry* g);   // status
-size_t workspace_counter_bytes(const Geometry& g);   // the fixed counter area
+size_t workspace_counter_bytes(const Geometry& g);   // the fixed area in front of the partial sums: counters, then pair words
+size_t pair_words(const Geometry& g);                // 64-bit words the pairwise reduction of this problem needs; 0: not offered
 int counter_stride(const Geometry& g);               // words between two row blocks' counters; 0: the plan does not fit
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }

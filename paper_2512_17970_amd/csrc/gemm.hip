@@ -55,7 +55,7 @@ int static_workspace(void** out, hipStream_t stream)
     if (!g_scratch_ptr[dev]) {
         void* ptr = nullptr;
         if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return CODEGEMM_LAUNCH_FAILED;
-        const int st = codegemm_workspace_init(ptr, (size_t)kCounterAreaWords * sizeof(uint32_t), stream);
+        const int st = codegemm_workspace_init(ptr, (size_t)kCounterAreaWords * sizeof(uint32_t) + kPairAreaBytes, stream);
         if (st) return st;
         g_scratch_ptr[dev] = ptr;
     }
@@ -129,8 +129,9 @@ static void fill_common(GemmParams* p, const Geometry& g, const void* x, void* w
 }
 
 static void fill_member(Member* mm, const Geometry& g, const uint8_t* packed_codes, const void* codebooks,
-                        const void* scales, void* y, float* partials, int blk0)
+                        const void* scales, void* y, float* partials, unsigned long long* pairs, int blk0)
 {
+    mm->pairs = pairs;
     mm->packed = packed_codes;
     mm->codebooks = static_cast<const _Float16*>(codebooks);
     mm->scales = g.g > 0 ? nullptr : static_cast<const _Float16*>(scales);
@@ -159,8 +160,12 @@ static int gemm_launch(const codegemm_desc* desc, const codegemm_plan* plan, con
 
     GemmParams p;
     fill_common(&p, g, x, workspace);
+    // the pairwise reduction where its words fit into their area, else ticket and partials
+    unsigned long long* pairs = reinterpret_cast<unsigned long long*>(static_cast<unsigned char*>(workspace) + (size_t)kCounterAreaWords * sizeof(uint32_t));
+    const size_t pw = pair_words(g);
+    if (pw == 0 || pw * 8 > kPairAreaBytes) pairs = nullptr;
     fill_member(&p.mem[0], g, packed_codes, codebooks, scales, y,
-                reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + cbytes), 0);
+                reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + cbytes), pairs, 0);
     return dispatch(g, p, static_cast<hipStream_t>(stream));
 }
 
@@ -278,10 +283,14 @@ extern "C" int codegemm_gemm_grouped(const codegemm_desc* desc, const codegemm_p
     fill_common(&p, whole, x, workspace);
     p.ngrp = count;
     float* partials = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + cbytes);
+    unsigned long long* pairs = reinterpret_cast<unsigned long long*>(static_cast<unsigned char*>(workspace) + (size_t)kCounterAreaWords * sizeof(uint32_t));
+    const size_t pw = pair_words(whole);               // whole.Npad is the sum over the members
+    if (pw == 0 || pw * 8 > kPairAreaBytes) pairs = nullptr;
     int blk0 = 0;
     for (int i = 0; i < count; ++i) {
         fill_member(&p.mem[i], members[i], group[i].packed_codes, group[i].codebooks, group[i].scales,
-                    group[i].y, partials, blk0);
+                    group[i].y, partials, pairs, blk0);
+        if (pairs) pairs += pair_words(members[i]);
         partials += (size_t)whole.B * whole.NKS * members[i].Npad;
         blk0 += members[i].NBLK;
     }

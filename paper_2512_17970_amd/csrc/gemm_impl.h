@@ -61,6 +61,7 @@ struct Member {
     const uint8_t* gscales;      // packed group scales (see codegemm_pack_scales), or nullptr
     void* y;
     float* partials;             // [B][NKS][Npad]
+    unsigned long long* pairs;   // [B][NKS - 1][Npad] words of the pairwise reduction, or nullptr: ticket and partials
     int N, NGR, Npad;
     int blk0;                    // first row block of this member in grid.y
 };
@@ -451,6 +452,63 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const Member& 
         return;
     }
 
+    if (mm.pairs) {
+        // Pairwise reduction that carries the data in the atomics themselves.  K ranges 2i and 2i + 1
+        // share a 64-bit word per output, zero between calls: each adds the bits of its fp32 partial
+        // to its own half (+0.0 travels as -0.0, so that a half that has arrived is never zero) with
+        // one device-scope add that returns the word as it was.  Whoever finds the other half there
+        // holds both values: it clears the word, adds the two in range order and goes on to the next
+        // level as range i; the other one is done.  One round trip per level, log2(NKS) levels, no
+        // wait for a store to land, no counter, no barrier; the order of the additions is fixed.
+        bool live[PER_THREAD];
+        unsigned long long* word[PER_THREAD];
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) {
+            const int o = tid + i * NT;
+            const int row = b0 + o / ROWS, nn = n_base + o % ROWS;
+            live[i] = o < BG * ROWS && row < p.B && nn < mm.N;
+            word[i] = mm.pairs + (size_t)(live[i] ? row : 0) * (p.NKS - 1) * mm.Npad + (live[i] ? nn : 0);
+        }
+        CG_STAMP(18);
+        int k = ks;
+        for (int span = p.NKS; span > 1; span >>= 1) {
+            const int side = k & 1;
+            unsigned long long old[PER_THREAD];
+#pragma unroll
+            for (int i = 0; i < PER_THREAD; ++i) {
+                uint32_t bits = __builtin_bit_cast(uint32_t, mine[i]);
+                if (bits == 0u) bits = 0x80000000u;
+                old[i] = 0;
+                if (live[i])
+                    old[i] = __hip_atomic_fetch_add(word[i] + (size_t)(k >> 1) * mm.Npad, (unsigned long long)bits << (32 * side),
+                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+            for (int i = 0; i < PER_THREAD; ++i) {
+                const uint32_t other = (uint32_t)(old[i] >> (32 * (side ^ 1)));
+                if (live[i] && other != 0u) {
+                    __hip_atomic_store(word[i] + (size_t)(k >> 1) * mm.Npad, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const float ov = __builtin_bit_cast(float, other);
+                    mine[i] = side ? ov + mine[i] : mine[i] + ov;
+                } else {
+                    live[i] = false;
+                }
+                word[i] += (size_t)(span >> 1) * mm.Npad;
+            }
+            if (span == p.NKS) CG_STAMP(19);
+            k >>= 1;
+        }
+        CG_STAMP(20);
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) {
+            const int o = tid + i * NT;
+            const int row = b0 + o / ROWS, nn = n_base + o % ROWS;
+            if (live[i]) store_y(row, nn, (mine[i] + 0.0f) * scale_of(i));
+        }
+        if (live[0]) CG_STAMP(3);
+        return;
+    }
+
     // K ranges are combined through the workspace.  Every datum that crosses workgroups
     // is moved by device-scope atomic accesses (write-through stores, cache-bypassing
     // loads, one RMW on the counter), so no L2 write-back / invalidate is needed: each
@@ -485,6 +543,15 @@ __device__ __forceinline__ void finish_block(const GemmParams& p, const Member& 
         const int row = b0 + o / ROWS, nn = n_base + o % ROWS;
         if (o >= BG * ROWS || row >= p.B || nn >= mm.N) continue;
         const float* src = mm.partials + (size_t)row * p.NKS * mm.Npad + nn;
+        if (p.NKS == 4) {
+            // the order of the pairwise reduction, so that a launch gives the same bits whichever protocol its size selects
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                v[j] = __hip_atomic_load(src + (size_t)j * mm.Npad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            store_y(row, nn, (((v[0] + v[1]) + (v[2] + v[3])) + 0.0f) * scale_of(i));
+            continue;
+        }
         float sum = 0.0f;
         int k2 = 0;
         for (; k2 + 32 <= p.NKS; k2 += 32) {            // 32 loads in flight, added in range order

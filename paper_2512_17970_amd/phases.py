@@ -19,7 +19,8 @@ PHASES = [  # (slot, label), in the order a workgroup passes them
     (8, "unit 0 gathered"), (9, "unit 1 gathered"), (10, "unit 2 gathered"), (11, "unit 3 gathered"),
     (12, "unit 4 gathered"), (13, "unit 5 gathered"), (14, "unit 6 gathered"), (15, "last unit gathered"),
     (4, "streaming loop done"), (16, "row totals staged"), (17, "staging barrier passed"),
-    (5, "partial sums issued"), (6, "partial sums acknowledged"), (7, "ticket drawn"), (3, "output stored"),
+    (5, "partial sums issued"), (6, "partial sums acknowledged"), (7, "ticket drawn"),
+    (18, "first pair add issued"), (19, "first pair add returned"), (20, "last pair add returned"), (3, "output stored"),
 ]
 
 

@@ -11,6 +11,7 @@ import paper_2512_17970_amd as cg
 from paper_2512_17970_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FIXED = 65536 + (2 << 20)        # what every workspace starts with: ticket counters, then the words of the pairwise reduction
 
 
 def header_symbols():
@@ -120,7 +121,7 @@ def test_default_plans_are_valid_for_all_workloads():
 
 
 def test_workspace_is_a_fixed_counter_area_plus_partial_sums():
-    """64 KB of ticket counters at a fixed place, then B x K ranges x padded rows fp32 partial sums; a plan
+    """64 KB of ticket counters and 2 MB of pair words at a fixed place, then B x K ranges x padded rows fp32 partial sums; a plan
     with several K ranges and more row blocks than the counter area has words is refused."""
     for (B, K, N, v, m, plan) in [(1, 8192, 8192, 8, 2, cg.Plan.make(8, 2, 8, 1)), (1, 8192, 28672, 8, 2, cg.Plan.make(16, 2, 4, 1)),
                                   (6, 4096, 1000, 4, 1, cg.Plan.make(16, 1, 5, 4)), (1, 512, 300, 8, 1, cg.Plan.make(8, 1, 1, 1))]:
@@ -128,7 +129,7 @@ def test_workspace_is_a_fixed_counter_area_plus_partial_sums():
         nkt = -(-(K // v) // 32)
         nks = min(plan.k_splits, nkt)
         nks = -(-nkt // -(-nkt // nks))
-        assert cg.codegemm_workspace_bytes(d, plan) == 65536 + B * nks * (-(-N // 128) * 128) * 4
+        assert cg.codegemm_workspace_bytes(d, plan) == FIXED + B * nks * (-(-N // 128) * 128) * 4
     many_rows = cg.Desc.make(1, 512, 128 * 20000, 8, 1)               # 20000 row blocks of 128 rows
     assert cg.codegemm_workspace_bytes(many_rows, cg.Plan.make(8, 1, 2, 1)) == 0
     assert cg.codegemm_workspace_bytes(many_rows, cg.Plan.make(8, 1, 1, 1)) > 0
@@ -206,21 +207,21 @@ def test_grouped_launch_host_validation():
     plan = cg.codegemm_default_plan(d)
     Ns = [8192, 1024, 1024]
     ws = cg.codegemm_grouped_workspace_bytes(d, plan, Ns)
-    # counter area + one fp32 partial per K range and padded row, member by member
+    # counter area + pair-word area + one fp32 partial per K range and padded row, member by member
     pad = sum(-(-n // 128) * 128 for n in Ns)
-    assert ws == 65536 + plan.k_splits * pad * 4
+    assert ws == FIXED + plan.k_splits * pad * 4
     assert cg.codegemm_grouped_workspace_bytes(d, None, Ns) == ws                       # NULL plan = default plan of the sum
     assert cg.codegemm_grouped_workspace_bytes(d, plan, [8192, 1024]) == 0              # heights do not add up
     assert cg.codegemm_grouped_workspace_bytes(d, plan, [8192, 1024, 512, 256, 256]) == 0   # more than four layers
     assert cg.codegemm_grouped_workspace_bytes(d, plan, [10240, 0]) == 0                # an empty layer
     d8 = cg.Desc.make(8, 8192, 10240, 8, 2)
-    assert cg.codegemm_grouped_workspace_bytes(d8, cg.Plan.make(8, 1, 2, 4), Ns) == 65536 + 8 * 2 * pad * 4   # batched-kernel plan
+    assert cg.codegemm_grouped_workspace_bytes(d8, cg.Plan.make(8, 1, 2, 4), Ns) == FIXED + 8 * 2 * pad * 4   # batched-kernel plan
     d64 = cg.Desc.make(64, 8192, 10240, 8, 2)
     assert cg.codegemm_grouped_workspace_bytes(d64, cg.Plan.make(8, 1, 1, 1), Ns) == 0  # more rows than one launch takes
     # ragged members are padded one by one
     d2 = cg.Desc.make(2, 1024, 130 + 129, 8, 2)
     p2 = cg.Plan.make(8, 1, 2, 2)
-    assert cg.codegemm_grouped_workspace_bytes(d2, p2, [130, 129]) == 65536 + 2 * 2 * 512 * 4
+    assert cg.codegemm_grouped_workspace_bytes(d2, p2, [130, 129]) == FIXED + 2 * 2 * 512 * 4
 
 
 def test_448_row_blocks_in_plans():
@@ -242,7 +243,7 @@ def test_448_row_blocks_in_plans():
     assert cg.codegemm_workspace_bytes(cg.Desc.make(8, 2048, 1000, 8, 2), cg.Plan.make(14, 2, 2, 4)) == 0
     assert cg.codegemm_workspace_bytes(cg.Desc.make(1, 2048, 1000, 8, 3), cg.Plan.make(14, 2, 2, 2)) == 0   # registers
     # build-only wavefronts: 16 wavefronts, two row words, one batch row, fp32 Psumbook, at most two codebooks
-    assert cg.codegemm_workspace_bytes(d, cg.Plan.make(16, 2, 2, 1, 0, 2)) == 65536 + 2 * 1024 * 4
+    assert cg.codegemm_workspace_bytes(d, cg.Plan.make(16, 2, 2, 1, 0, 2)) == FIXED + 2 * 1024 * 4
     assert cg.codegemm_workspace_bytes(d, cg.Plan.make(16, 1, 2, 1, 0, 2)) == 0
     assert cg.codegemm_workspace_bytes(d, cg.Plan.make(8, 2, 2, 1, 0, 2)) == 0
     assert cg.codegemm_workspace_bytes(d, cg.Plan.make(16, 2, 2, 1, 0, 1)) == 0

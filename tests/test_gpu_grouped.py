@@ -83,6 +83,15 @@ def test_grouped_batched_kernel(K, Ns, v, m, B, g, plan):
     assert pl.batch_group == 4, pl
 
 
+@pytest.mark.parametrize("plan", [(8, 1, 4, 1), (16, 2, 4, 2), (16, 2, 2, 1)])
+def test_grouped_and_single_calls_agree_across_reduction_protocols(plan):
+    """Two or four K ranges are combined pairwise through 64-bit words when the words of the launch fit into their
+    fixed area, else by ticket and partial sums.  Here each member alone fits and the group does not (two batch
+    rows, 2 x 3 x 8 bytes per padded row with four ranges): the bits must agree all the same."""
+    Ns = [40000, 40000] if plan[2] == 4 else [70000, 70000]
+    run_group(1024, Ns, 8, 1, 2, -1, plan=cg.Plan.make(*plan), seed=7300)
+
+
 def test_grouped_null_plan_is_the_default_plan_of_the_sum():
     K, Ns = 2048, [900, 300, 300]
     desc = cg.Desc.make(1, K, sum(Ns), 8, 2)
