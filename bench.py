@@ -514,7 +514,7 @@ def main():
         dom_us = sum(r["us_cold_median"] for r in dom) / len(dom)
         dom_bytes = sum(r["compressed_bytes"] for r in dom) / len(dom)
         out["roofline"]["dominant_shapes"] = {
-            "cases": [r["case"] for r in dom], "plans": sorted({r["plan"] for r in dom}),
+            "cases": [r["case"] for r in dom], "plans": [r["plan"] for r in dom],
             "avg_launch_us": round(dom_us, 3), "algorithmic_bytes_per_launch": dom_bytes,
             "achieved": dom_bytes / dom_us * 1e-3, "frac": dom_bytes / dom_us * 1e-3 / HBM_PEAK_GBPS,
             "note": "median of 5 graph replays of 200 cold calls per shape, HIP events: the time per call includes the "

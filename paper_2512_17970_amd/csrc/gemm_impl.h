@@ -100,9 +100,10 @@ __device__ __forceinline__ Member member_of(const GemmParams& p, int grid_blk)
 // (-mllvm -amdgpu-kernarg-preload-count): the leading scalar arguments arrive in scalar
 // registers with the wavefront, so the first loads go out without a round trip to the
 // kernel-argument segment (measured with a probe kernel: 260-300 clocks median, 630 for the
-// slowest workgroup, against 8).  Structs are not preloaded, hence the copies; firmware without
+// slowest workgroup, against 8).  Structs are not preloaded, hence the copies (the fp16 pointers
+// travel as void*, which keeps the kernel names readable in profiler output); firmware without
 // the feature falls back to loading them, which the compiler arranges.
-#define CG_HEAD_PARAMS const _Float16* hx, const uint8_t* hpacked, const _Float16* hcodebooks, const uint8_t* hgscales, \
+#define CG_HEAD_PARAMS const void* hx, const uint8_t* hpacked, const void* hcodebooks, const uint8_t* hgscales, \
                        int hK, int hNKT, int hKPW, int hB, int hNGR, int hmisc
 #define CG_HEAD_ARGS(p) (p).x, (p).mem[0].packed, (p).mem[0].codebooks, (p).mem[0].gscales, (p).K, (p).NKT, (p).KPW, (p).B, \
                         (p).mem[0].NGR, ((p).ngrp | ((p).gshift << 8) | ((p).GPU << 16))
@@ -111,9 +112,9 @@ __device__ __forceinline__ Member member_of(const GemmParams& p, int grid_blk)
 __device__ __forceinline__ GemmParams with_head(const GemmParams& pk, CG_HEAD_PARAMS)
 {
     GemmParams p = pk;
-    p.x = hx; p.K = hK; p.NKT = hNKT; p.KPW = hKPW; p.B = hB;
+    p.x = static_cast<const _Float16*>(hx); p.K = hK; p.NKT = hNKT; p.KPW = hKPW; p.B = hB;
     p.ngrp = hmisc & 0xff; p.gshift = (hmisc >> 8) & 0xff; p.GPU = (int)((unsigned)hmisc >> 16);
-    p.mem[0].packed = hpacked; p.mem[0].codebooks = hcodebooks; p.mem[0].gscales = hgscales;
+    p.mem[0].packed = hpacked; p.mem[0].codebooks = static_cast<const _Float16*>(hcodebooks); p.mem[0].gscales = hgscales;
     p.mem[0].NGR = hNGR; p.mem[0].blk0 = 0;
     return p;
 }
